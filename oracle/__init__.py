@@ -1,0 +1,14 @@
+"""CPU fp64 oracle for sliced, asymmetric-unit causal attention.  TEST INFRASTRUCTURE ONLY.
+
+Everything here is a plain, slow, obviously-correct statement of what the GPU
+library must compute; it exists so that tests, the smoke check and the
+benchmark's `cpu_baseline` leg can compare against it.  The product path never
+imports it, and it imports nothing from the product path.
+
+Parity pins (all in tests/, CPU-only): library cross-check against PyTorch's
+fp64 scaled-dot-product attention with autograd, central finite differences,
+closed forms (zero queries, single-token samples, key shift), row-sum and
+gradient-sum identities, slicing/grouping invariance, brute-force table
+enumeration and hand-written fixtures under tests/golden/.  No function in
+this package is "parity unpinned".
+"""
