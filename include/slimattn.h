@@ -1,0 +1,189 @@
+/*
+ * libslimattn -- memory-efficient causal attention, forward and backward, over fine-grained
+ * slices of variable-length packed samples, with separate forward and backward unit lists.
+ * One MI355X (gfx950), hand-written HIP.  C ABI: plain pointers and sizes only.
+ *
+ * Problem statement (SlimPack, arxiv 2509.26246):
+ *   - samples are cut into slices by exploiting causality (Balanced Packing & Asymmetric
+ *     Partitioning Solver subsection); a slice is a run of consecutive query rows of one sample;
+ *   - a scheduling unit (the paper's MicroPack) is a list of slices: consecutive slices of one
+ *     long sample, whole short samples, or a mix (SlimPack System section);
+ *   - the forward pass and the backward pass use different unit lists (Asymmetric Partition);
+ *   - a slice's queries attend to the keys/values of every earlier slice of the same sample (the
+ *     KV cache) and causally to the slice itself (PackFlow Pipeline Parallelism Scheduling);
+ *   - the backward pass recomputes the scores from q, k and a saved row statistic (Asymmetric
+ *     Cost Profile paragraph) and a slice's dK/dV collect contributions from every later slice
+ *     (DAG simulator, inter-slice dependencies).
+ *
+ * Tensor layouts (token-major, packed): q, o, dO, dQ : [T, Hq, d];  k, v, dK, dV : [T, Hkv, d];
+ * lse : [Hq, T] float.  Query head h uses KV head h / (Hq / Hkv).
+ *
+ * Pointer kinds are stated per argument: HOST = ordinary host memory, DEVICE = memory of the
+ * current HIP device (allocated and owned by the caller; the library never frees it).
+ *
+ * Every function returns SLIMATTN_OK (0) or a negative SLIMATTN_E* code; nothing throws, aborts
+ * or synchronises the device unless stated.  Compute calls are asynchronous on the given stream.
+ */
+#ifndef SLIMATTN_H
+#define SLIMATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLIMATTN_OK       0
+#define SLIMATTN_EINVAL  -1   /* null / misaligned pointer, unsupported head_dim, dtype, Hq % Hkv != 0, bad range */
+#define SLIMATTN_ETABLE  -2   /* tables inconsistent (see slimattn_validate) */
+#define SLIMATTN_ECAP    -3   /* an output array is too small */
+#define SLIMATTN_EHIP    -4   /* a HIP call failed; code via slimattn_last_hip_error() */
+#define SLIMATTN_ENOMEM  -5   /* host allocation failed */
+
+#define SLIMATTN_F32   0      /* q,k,v,o,dO,dQ,dK,dV are float; all arithmetic fp32 */
+#define SLIMATTN_BF16  1      /* tensors are bf16; products on bf16 MFMA, fp32 accumulation and softmax */
+
+/* One slice of one sample.  q_start is a global token index; kv_start is the first token of the
+ * sample; kv_len = q_start + q_len - kv_start is the number of keys the slice can see. */
+typedef struct slimattn_slice {
+  int32_t sample, idx_in_sample, q_start, q_len, kv_start, kv_len, rsv0, rsv1;
+} slimattn_slice;
+
+/* Grouping policies of the host-side unit builder.  All are deterministic.  "Walk order": samples
+ * by descending length (ties: lower index first; the paper sorts samples by descending forward
+ * cost), each sample's slices ascending (forward) or descending (backward: first-in, last-out).
+ * cost(slice) = w_quad * pairs + w_lin * q_len, pairs = visible (query, key) pairs. */
+#define SLIMATTN_POLICY_ALL           0  /* one unit holding every slice in table order */
+#define SLIMATTN_POLICY_PER_SAMPLE    1  /* one unit per sample; slices descend if backward != 0 */
+#define SLIMATTN_POLICY_ROUND_ROBIN   2  /* slice t -> unit t mod m; units listed descending if descending != 0 */
+#define SLIMATTN_POLICY_PREFIX_FILL   3  /* walk order; slice with cost interval [C, C+c) -> unit floor(m(2C+c)/(2W)),
+                                            clamped to m-1: the paper's per-unit target W/m with a midpoint rule */
+#define SLIMATTN_POLICY_TOKEN_CAP     4  /* walk order; next-fit, a unit is closed when the next slice would push it
+                                            over `cap` query tokens */
+#define SLIMATTN_POLICY_SEEDED_LPT    5  /* every slice of a multi-slice sample seeds its own unit; single-slice
+                                            samples, in walk order, each join the currently cheapest unit */
+#define SLIMATTN_POLICY_ISOLATE_FILL  6  /* slices with cost*m*theta_den >= theta_num*W become singleton units; the
+                                            rest are PREFIX_FILLed into max(1, m - n_isolated) units; an isolated
+                                            slice closes the unit that is open at its place in the walk */
+
+typedef struct slimattn_policy {
+  int32_t kind;
+  int32_t m;            /* target number of units (ROUND_ROBIN, PREFIX_FILL, ISOLATE_FILL) */
+  int64_t w_quad;       /* cost weights */
+  int64_t w_lin;
+  int32_t backward;     /* walk a sample's slices in descending order */
+  int32_t descending;   /* ROUND_ROBIN: list each unit's slices in descending table order */
+  int32_t cap;          /* TOKEN_CAP */
+  int32_t m_min;        /* SEEDED_LPT: at least this many units before filling */
+  int32_t theta_num, theta_den;   /* ISOLATE_FILL threshold as a fraction */
+} slimattn_policy;
+
+typedef struct slimattn_params {
+  int32_t total_tokens;      /* T */
+  int32_t n_q_heads;         /* Hq */
+  int32_t n_kv_heads;        /* Hkv, divides Hq */
+  int32_t head_dim;          /* d: 64 or 128 (bf16); any multiple of 4 up to 128 (f32) */
+  int32_t dtype;             /* SLIMATTN_F32 or SLIMATTN_BF16 */
+  float   scale;             /* softmax scale applied to q.k */
+  int32_t unit_lo, unit_hi;  /* run units [unit_lo, unit_hi) of the pass's list; unit_hi = -1 means all */
+  int32_t flags;             /* SLIMATTN_FLAG_* */
+} slimattn_params;
+
+#define SLIMATTN_FLAG_PER_UNIT_LAUNCH 1  /* one launch per unit instead of one fused launch over the range */
+
+#define SLIMATTN_CHECK_FORWARD   0
+#define SLIMATTN_CHECK_BACKWARD  1
+#define SLIMATTN_CHECK_ORDER     2       /* also enforce the paper's pipeline order rules */
+
+typedef struct slimattn_tables slimattn_tables;   /* opaque: host + device copies of all tables */
+
+/* ---- host-side unit-descriptor builder (no GPU needed) ------------------------------------- */
+
+/* Cut every sample into slices of `slice_size` rows from its start (last one may be short).
+ * lengths HOST [n]; cu_out HOST [n+1] (cumulative starts); out HOST [cap]; n_slices HOST out.
+ * ECAP if cap is too small (n_slices still receives the needed count); EINVAL on a length < 0
+ * or slice_size < 1 or total tokens beyond int32. */
+int slimattn_build_slices(const int32_t* lengths, int32_t n, int32_t slice_size, int32_t* cu_out,
+                          slimattn_slice* out, int32_t cap, int32_t* n_slices);
+
+/* Same, from explicit interior cut points: sample s is cut at bounds[bounds_ptr[s] .. bounds_ptr[s+1])
+ * (strictly increasing, inside (0, L)).  All arrays HOST. */
+int slimattn_build_slices_from_bounds(const int32_t* lengths, int32_t n, const int32_t* bounds_ptr,
+                                      const int32_t* bounds, int32_t* cu_out, slimattn_slice* out,
+                                      int32_t cap, int32_t* n_slices);
+
+/* Group slices into units for one pass.  unit_ptr HOST [cap_units+1], unit_slices HOST [n_slices]
+ * (CSR: unit u holds unit_slices[unit_ptr[u] .. unit_ptr[u+1])); empty units are dropped.
+ * cu HOST [n+1].  ECAP if cap_units is too small; EINVAL on a bad policy. */
+int slimattn_build_units(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                         const slimattn_policy* policy, int32_t* unit_ptr, int32_t* unit_slices,
+                         int32_t cap_units, int32_t* n_units);
+
+/* Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear
+ * in ascending order in the table, are non-empty and tile [0, L) exactly; kv_start/kv_len agree
+ * with cu; unit_ptr is a valid CSR over unit_slices; every slice is in exactly one unit.
+ * With SLIMATTN_CHECK_ORDER in `mode`: along a sample the unit index never decreases with the
+ * slice index (forward) / never increases (SLIMATTN_CHECK_BACKWARD), and inside a unit a sample's
+ * slices are adjacent in that order.  Returns OK or ETABLE; *rule (optional, HOST) receives a
+ * static string naming the first violated rule.  All arrays HOST. */
+int slimattn_validate(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                      const int32_t* unit_ptr, const int32_t* unit_slices, int32_t n_units, int mode,
+                      const char** rule);
+
+/* Visible (query, key) pairs of a slice, and the forward/backward flop counts the paper's
+ * 1 : 2.5 ratio rests on: 2 resp. 5 tile products of 2*d*Hq flops per pair. */
+int64_t slimattn_slice_pairs(const slimattn_slice* s);
+int64_t slimattn_flops_fwd(int64_t pairs, int32_t head_dim, int32_t n_q_heads);
+int64_t slimattn_flops_bwd(int64_t pairs, int32_t head_dim, int32_t n_q_heads);
+
+/* ---- tables on the device -------------------------------------------------------------------- */
+
+/* Validates (structural rules, both lists), derives the private tile work-lists and copies
+ * everything to the current device with one synchronous upload.  All inputs HOST; they are copied.
+ * *out receives a handle to free with slimattn_tables_destroy.  ETABLE / EHIP / ENOMEM. */
+int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                           const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
+                           const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
+                           slimattn_tables** out);
+void slimattn_tables_destroy(slimattn_tables* t);
+
+/* Counts held by a handle: what = 0 tokens, 1 samples, 2 slices, 3 forward units, 4 backward units. */
+int64_t slimattn_tables_count(const slimattn_tables* t, int what);
+
+/* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators + row statistic). */
+size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t n_q_heads, int32_t n_kv_heads,
+                                    int32_t head_dim);
+
+/* ---- compute ------------------------------------------------------------------------------- */
+
+/* Forward over units [unit_lo, unit_hi) of the forward list: for every query row i of every slice
+ * in those units and every head, S_ij = scale * q_i . k_j over the sample's keys j <= i,
+ * lse_i = log sum_j exp S_ij, o_i = sum_j exp(S_ij - lse_i) v_j.  Rows of slices outside the unit
+ * range are not written.  q, k, v DEVICE (read), o, lse DEVICE (written), 16-byte aligned.
+ * stream: a hipStream_t (NULL = default stream).  Allocates nothing, does not synchronise. */
+int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v,
+                 const slimattn_tables* t, void* o, float* lse, void* stream);
+
+/* Backward over units [unit_lo, unit_hi) of the backward list, with the scores recomputed from q, k
+ * and lse: P_ij = exp(S_ij - lse_i), dP_ij = dO_i . v_j, delta_i = dO_i . o_i,
+ * dS_ij = P_ij (dP_ij - delta_i); dQ_i = scale sum_j dS_ij k_j for the rows of the range's slices;
+ * dK_j += scale sum_i dS_ij q_i and dV_j += sum_i P_ij dO_i over those rows i >= j and over the
+ * query heads of j's group, accumulated in fp32 in `workspace` in a fixed order (no float
+ * atomics; bitwise repeatable).  A call with unit_lo == 0 clears the accumulators first; the
+ * call whose unit_hi reaches the end of the list converts them into dK, dV.  A caller that
+ * splits the list over several calls passes the same workspace to each, in list order.
+ * q, k, v, o, lse, dO DEVICE (read); dQ, dK, dV DEVICE (written); workspace DEVICE of at least
+ * slimattn_bwd_workspace_bytes().  Allocates nothing, does not synchronise. */
+int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o,
+                 const float* lse, const void* dO, const slimattn_tables* t, void* dQ, void* dK,
+                 void* dV, void* workspace, void* stream);
+
+const char* slimattn_strerror(int code);
+int slimattn_last_hip_error(void);       /* hipError_t of the last EHIP on this thread */
+int slimattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMATTN_H */

@@ -67,6 +67,8 @@ def build_slices_from_bounds(lengths: Sequence[int], bounds: Sequence[Sequence[i
         cu.append(cu[-1] + int(L))
     rows = []
     for s, L in enumerate(lengths):
+        if int(L) == 0:
+            continue                               # an empty sample has no slices
         cuts = [0] + [int(c) for c in bounds[s]] + [int(L)]
         for idx in range(len(cuts) - 1):
             a, b = cuts[idx], cuts[idx + 1]

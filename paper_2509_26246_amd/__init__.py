@@ -1,0 +1,16 @@
+"""libslimattn: sliced, asymmetric-unit causal attention for one MI355X (gfx950).
+
+The package is a thin ctypes binding over the C-ABI library declared in include/slimattn.h.
+Every step of the hot path runs in the library's HIP kernels; Python only marshals arguments.
+Importing the package does not load the library; the first call does, and fails loudly if it
+has not been built (python -m paper_2509_26246_amd.build).
+"""
+from .binding import (SlimAttnError, Tables, build_slices, build_slices_from_bounds, build_units, validate,
+                      slice_pairs, flops_fwd, flops_bwd, tables_create, bwd_workspace_bytes, fwd, bwd, strerror,
+                      version, load_library, POLICY_KINDS, F32, BF16, FLAG_PER_UNIT_LAUNCH, CHECK_FORWARD,
+                      CHECK_BACKWARD, CHECK_ORDER, EXPORTED_SYMBOLS)
+
+__all__ = ["SlimAttnError", "Tables", "build_slices", "build_slices_from_bounds", "build_units", "validate",
+           "slice_pairs", "flops_fwd", "flops_bwd", "tables_create", "bwd_workspace_bytes", "fwd", "bwd",
+           "strerror", "version", "load_library", "POLICY_KINDS", "F32", "BF16", "FLAG_PER_UNIT_LAUNCH",
+           "CHECK_FORWARD", "CHECK_BACKWARD", "CHECK_ORDER", "EXPORTED_SYMBOLS"]

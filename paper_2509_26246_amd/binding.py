@@ -1,0 +1,243 @@
+"""ctypes binding with the same names as the C ABI (include/slimattn.h).  Marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libslimattn.so")
+
+F32, BF16 = 0, 1
+FLAG_PER_UNIT_LAUNCH = 1
+CHECK_FORWARD, CHECK_BACKWARD, CHECK_ORDER = 0, 1, 2
+POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "TOKEN_CAP": 4, "SEEDED_LPT": 5,
+                "ISOLATE_FILL": 6}
+EXPORTED_SYMBOLS = [
+    "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
+    "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
+    "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
+    "slimattn_bwd", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version"]
+
+
+class SlimAttnError(RuntimeError):
+    def __init__(self, code: int, where: str, extra: str = ""):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code}){extra}")
+
+
+class _Policy(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("m", C.c_int32), ("w_quad", C.c_int64), ("w_lin", C.c_int64),
+                ("backward", C.c_int32), ("descending", C.c_int32), ("cap", C.c_int32), ("m_min", C.c_int32),
+                ("theta_num", C.c_int32), ("theta_den", C.c_int32)]
+
+
+class _Params(C.Structure):
+    _fields_ = [("total_tokens", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float), ("unit_lo", C.c_int32),
+                ("unit_hi", C.c_int32), ("flags", C.c_int32)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libslimattn.so; raises if it has not been built.  There is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_26246_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+    lib.slimattn_build_slices.argtypes = [i32p, C.c_int32, C.c_int32, i32p, vp, C.c_int32, i32p]
+    lib.slimattn_build_slices_from_bounds.argtypes = [i32p, C.c_int32, i32p, i32p, i32p, vp, C.c_int32, i32p]
+    lib.slimattn_build_units.argtypes = [i32p, C.c_int32, vp, C.c_int32, C.POINTER(_Policy), i32p, i32p, C.c_int32, i32p]
+    lib.slimattn_validate.argtypes = [i32p, C.c_int32, vp, C.c_int32, i32p, i32p, C.c_int32, C.c_int, C.POINTER(C.c_char_p)]
+    lib.slimattn_slice_pairs.argtypes = [vp]
+    lib.slimattn_slice_pairs.restype = C.c_int64
+    for f in (lib.slimattn_flops_fwd, lib.slimattn_flops_bwd):
+        f.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        f.restype = C.c_int64
+    lib.slimattn_tables_create.argtypes = [i32p, C.c_int32, vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32,
+                                           C.POINTER(vp)]
+    lib.slimattn_tables_destroy.argtypes = [vp]
+    lib.slimattn_tables_destroy.restype = None
+    lib.slimattn_tables_count.argtypes = [vp, C.c_int]
+    lib.slimattn_tables_count.restype = C.c_int64
+    lib.slimattn_bwd_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32]
+    lib.slimattn_bwd_workspace_bytes.restype = C.c_size_t
+    lib.slimattn_fwd.argtypes = [C.POINTER(_Params), vp, vp, vp, vp, vp, vp, vp]
+    lib.slimattn_bwd.argtypes = [C.POINTER(_Params)] + [vp] * 12
+    lib.slimattn_strerror.argtypes = [C.c_int]
+    lib.slimattn_strerror.restype = C.c_char_p
+    lib.slimattn_last_hip_error.restype = C.c_int
+    lib.slimattn_version.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def strerror(code: int) -> str:
+    return load_library().slimattn_strerror(code).decode()
+
+
+def version() -> int:
+    return load_library().slimattn_version()
+
+
+def build_slices(lengths: Sequence[int], slice_size: int) -> Tuple[np.ndarray, np.ndarray]:
+    lib = load_library()
+    L = _i32(lengths)
+    cu = np.zeros(len(L) + 1, np.int32)
+    n = C.c_int32(0)
+    rc = lib.slimattn_build_slices(_p(L), len(L), slice_size, _p(cu), None, 0, C.byref(n))
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_build_slices")
+    out = np.zeros((n.value, 8), np.int32)
+    rc = lib.slimattn_build_slices(_p(L), len(L), slice_size, _p(cu), out.ctypes.data, n.value, C.byref(n))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_build_slices")
+    return cu, out
+
+
+def build_slices_from_bounds(lengths: Sequence[int], bounds: Sequence[Sequence[int]]):
+    lib = load_library()
+    L = _i32(lengths)
+    ptr = _i32(np.concatenate([[0], np.cumsum([len(b) for b in bounds])]))
+    flat = _i32([x for b in bounds for x in b] or [0])
+    cu = np.zeros(len(L) + 1, np.int32)
+    cap = len(L) + len(flat) + 1
+    out = np.zeros((cap, 8), np.int32)
+    n = C.c_int32(0)
+    rc = lib.slimattn_build_slices_from_bounds(_p(L), len(L), _p(ptr), _p(flat), _p(cu), out.ctypes.data, cap, C.byref(n))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_build_slices_from_bounds")
+    return cu, out[:n.value].copy()
+
+
+def build_units(cu, slices, policy: str, **p) -> Tuple[np.ndarray, np.ndarray]:
+    lib = load_library()
+    cu, slices = _i32(cu), _i32(slices).reshape(-1, 8)
+    pol = _Policy(kind=POLICY_KINDS[policy], m=int(p.get("m", 0)), w_quad=int(p.get("w_quad", 0)),
+                  w_lin=int(p.get("w_lin", 0)), backward=int(bool(p.get("backward", False))),
+                  descending=int(bool(p.get("descending", False))), cap=int(p.get("cap", 0)),
+                  m_min=int(p.get("m_min", 1)), theta_num=int(p.get("theta_num", 1)), theta_den=int(p.get("theta_den", 1)))
+    ns = len(slices)
+    ptr = np.zeros(ns + 2, np.int32)
+    flat = np.zeros(max(ns, 1), np.int32)
+    nu = C.c_int32(0)
+    rc = lib.slimattn_build_units(_p(cu), len(cu) - 1, slices.ctypes.data, ns, C.byref(pol), _p(ptr), _p(flat), ns + 1,
+                                  C.byref(nu))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_build_units")
+    return ptr[:nu.value + 1].copy(), flat[:ns].copy()
+
+
+def validate(cu, slices, unit_ptr, unit_slices, mode: int = CHECK_FORWARD) -> Tuple[int, str]:
+    lib = load_library()
+    cu, slices = _i32(cu), _i32(slices).reshape(-1, 8)
+    up, us = _i32(unit_ptr), _i32(unit_slices)
+    rule = C.c_char_p()
+    rc = lib.slimattn_validate(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(up), _p(us), len(up) - 1, mode,
+                               C.byref(rule))
+    return rc, (rule.value or b"").decode()
+
+
+def slice_pairs(rec) -> int:
+    r = _i32(rec)
+    return int(load_library().slimattn_slice_pairs(r.ctypes.data))
+
+
+def flops_fwd(pairs: int, head_dim: int, n_q_heads: int) -> int:
+    return int(load_library().slimattn_flops_fwd(pairs, head_dim, n_q_heads))
+
+
+def flops_bwd(pairs: int, head_dim: int, n_q_heads: int) -> int:
+    return int(load_library().slimattn_flops_bwd(pairs, head_dim, n_q_heads))
+
+
+class Tables:
+    """Owns a slimattn_tables handle (device copies of the tables on the current device)."""
+
+    def __init__(self, handle: int, n_fwd_units: int, n_bwd_units: int, total_tokens: int):
+        self.handle = handle
+        self.n_fwd_units, self.n_bwd_units, self.total_tokens = n_fwd_units, n_bwd_units, total_tokens
+
+    def count(self, what: int) -> int:
+        return int(load_library().slimattn_tables_count(self.handle, what))
+
+    def destroy(self):
+        if self.handle:
+            load_library().slimattn_tables_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def tables_create(cu, slices, fwd_unit_ptr, fwd_unit_slices, bwd_unit_ptr, bwd_unit_slices) -> Tables:
+    lib = load_library()
+    cu, slices = _i32(cu), _i32(slices).reshape(-1, 8)
+    fp, fs, bp, bs = _i32(fwd_unit_ptr), _i32(fwd_unit_slices), _i32(bwd_unit_ptr), _i32(bwd_unit_slices)
+    h = C.c_void_p()
+    rc = lib.slimattn_tables_create(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(fp), _p(fs), len(fp) - 1,
+                                    _p(bp), _p(bs), len(bp) - 1, C.byref(h))
+    if rc != 0:
+        extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
+        raise SlimAttnError(rc, "slimattn_tables_create", extra)
+    return Tables(h.value, len(fp) - 1, len(bp) - 1, int(cu[-1]))
+
+
+def bwd_workspace_bytes(tables: Tables, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:
+    return int(load_library().slimattn_bwd_workspace_bytes(tables.handle, n_q_heads, n_kv_heads, head_dim))
+
+
+def _ptr(t) -> int:
+    """Device pointer of a torch tensor (must be contiguous) or a raw integer address."""
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _params(T, hq, hkv, d, dtype, scale, unit_lo, unit_hi, flags):
+    return _Params(total_tokens=T, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=dtype, scale=scale,
+                   unit_lo=unit_lo, unit_hi=unit_hi, flags=flags)
+
+
+def fwd(q, k, v, tables: Tables, o, lse, *, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, scale: float,
+        unit_lo: int = 0, unit_hi: int = -1, flags: int = 0, stream: Optional[int] = None) -> None:
+    """slimattn_fwd: q,k,v -> o,lse on `stream` (a hipStream_t address; None = default stream)."""
+    lib = load_library()
+    prm = _params(tables.total_tokens, n_q_heads, n_kv_heads, head_dim, dtype, scale, unit_lo, unit_hi, flags)
+    rc = lib.slimattn_fwd(C.byref(prm), _ptr(q), _ptr(k), _ptr(v), tables.handle, _ptr(o), _ptr(lse), stream)
+    if rc != 0:
+        extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
+        raise SlimAttnError(rc, "slimattn_fwd", extra)
+
+
+def bwd(q, k, v, o, lse, dO, tables: Tables, dQ, dK, dV, workspace, *, n_q_heads: int, n_kv_heads: int, head_dim: int,
+        dtype: int, scale: float, unit_lo: int = 0, unit_hi: int = -1, flags: int = 0,
+        stream: Optional[int] = None) -> None:
+    """slimattn_bwd: q,k,v,o,lse,dO -> dQ,dK,dV on `stream`."""
+    lib = load_library()
+    prm = _params(tables.total_tokens, n_q_heads, n_kv_heads, head_dim, dtype, scale, unit_lo, unit_hi, flags)
+    rc = lib.slimattn_bwd(C.byref(prm), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), tables.handle,
+                          _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), stream)
+    if rc != 0:
+        extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
+        raise SlimAttnError(rc, "slimattn_bwd", extra)

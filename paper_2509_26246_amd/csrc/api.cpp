@@ -1,0 +1,147 @@
+// Entry points slimattn_fwd / slimattn_bwd: argument checks, scope selection, launches.
+// No device allocation and no synchronisation happens here.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace slimattn {
+int& last_hip_error();
+
+namespace {
+
+bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int check_common(const slimattn_params* p, const slimattn_tables* t, int pass, int* lo, int* hi) {
+  if (!p || !t) return SLIMATTN_EINVAL;
+  if (p->dtype != SLIMATTN_F32 && p->dtype != SLIMATTN_BF16) return SLIMATTN_EINVAL;
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0 || p->n_q_heads > 65535) return SLIMATTN_EINVAL;
+  const int d = p->head_dim;
+  if (p->dtype == SLIMATTN_BF16 ? !(d == 64 || d == 128) : !(d == 16 || d == 32 || d == 64 || d == 128)) return SLIMATTN_EINVAL;
+  if ((int64_t)p->total_tokens != t->total_tokens) return SLIMATTN_EINVAL;
+  if (!(p->scale == p->scale)) return SLIMATTN_EINVAL;
+  *lo = p->unit_lo;
+  *hi = p->unit_hi < 0 ? t->n_units[pass] : p->unit_hi;
+  if (*lo < 0 || *hi > t->n_units[pass] || *lo > *hi) return SLIMATTN_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != t->device) return SLIMATTN_EINVAL;
+  return SLIMATTN_OK;
+}
+
+int hip_rc(int e) {
+  if (e == 0) return SLIMATTN_OK;
+  last_hip_error() = e;
+  return SLIMATTN_EHIP;
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
+
+}  // namespace
+}  // namespace slimattn
+
+using namespace slimattn;
+
+extern "C" {
+
+int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v, const slimattn_tables* t,
+                 void* o, float* lse, void* stream) {
+  int lo, hi;
+  int rc = check_common(p, t, 0, &lo, &hi);
+  if (rc != SLIMATTN_OK) return rc;
+  if (t->total_tokens == 0 || lo == hi) return SLIMATTN_OK;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return SLIMATTN_EINVAL;
+  const int z = tile_index(fwd_q_tile(p->dtype, p->head_dim));
+  const LaunchCtx ctx{p, stream, t->total_tokens};
+  auto run = [&](const QItem* items, int n) -> int {
+    return p->dtype == SLIMATTN_F32
+               ? launch_fwd_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (float*)o, lse, items, n)
+               : launch_fwd_bf16(ctx, q, k, v, o, lse, items, n);
+  };
+  const bool whole = lo == 0 && hi == t->n_units[0];
+  if (whole && !(p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH))
+    return hip_rc(run(t->d_fused.q_items[z], (int)t->fused.q_items[z].size()));
+  const auto& off = t->per_unit[0].q_off[z];
+  if (!(p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH))
+    return hip_rc(run(t->d_per_unit[0].q_items[z] + off[lo], off[hi] - off[lo]));
+  for (int u = lo; u < hi; ++u) {
+    rc = hip_rc(run(t->d_per_unit[0].q_items[z] + off[u], off[u + 1] - off[u]));
+    if (rc != SLIMATTN_OK) return rc;
+  }
+  return SLIMATTN_OK;
+}
+
+int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                 const void* dO, const slimattn_tables* t, void* dQ, void* dK, void* dV, void* workspace, void* stream) {
+  int lo, hi;
+  int rc = check_common(p, t, 1, &lo, &hi);
+  if (rc != SLIMATTN_OK) return rc;
+  if (t->total_tokens == 0 || lo == hi) return SLIMATTN_OK;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dO) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return SLIMATTN_EINVAL;
+  const bool f32 = p->dtype == SLIMATTN_F32;
+  const size_t T = (size_t)t->total_tokens;
+  const size_t acc_elems = T * p->n_kv_heads * p->head_dim;
+  float* acc_dk = (float*)workspace;
+  float* acc_dv = acc_dk + acc_elems;
+  float* delta = (float*)((char*)workspace + align_up(2 * acc_elems * sizeof(float)));
+  const LaunchCtx ctx{p, stream, t->total_tokens};
+  const int n_units = t->n_units[1];
+  const bool whole = lo == 0 && hi == n_units;
+  const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
+
+  if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
+    rc = hip_rc(f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
+                    : launch_bwd_delta_bf16(ctx, o, dO, delta));
+    if (rc != SLIMATTN_OK) return rc;
+  }
+  const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
+  const int zk = tile_index(dkdv_kv_tile(p->dtype, p->head_dim));
+  auto run_dq = [&](const QItem* items, int n) -> int {
+    return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
+                                   (float*)dQ, items, n)
+               : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse, delta, dQ, items, n);
+  };
+  auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {
+    return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
+                                     acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc, store_final)
+               : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                                      store_final);
+  };
+
+  if (whole && !per_unit) {
+    // One scope holding every slice: each key tile's owner sums all later query rows itself and
+    // writes dK/dV directly; the fp32 accumulators in the workspace are not touched.
+    rc = hip_rc(run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1));
+    if (rc != SLIMATTN_OK) return rc;
+    return hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
+  }
+
+  const auto& qoff = t->per_unit[1].q_off[zq];
+  const auto& koff = t->per_unit[1].kv_off[zk];
+  if (lo == 0) {
+    rc = hip_rc(launch_fill_zero(ctx, acc_dk, (int64_t)(2 * acc_elems)));
+    if (rc != SLIMATTN_OK) return rc;
+  }
+  if (!per_unit) {
+    rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[lo], qoff[hi] - qoff[lo]));
+    if (rc != SLIMATTN_OK) return rc;
+  }
+  for (int u = lo; u < hi; ++u) {
+    // Units run one after another on the stream; each adds its queries' contributions to the
+    // accumulators of every key tile of the prefix it sees (read-modify-write by the tile's
+    // single owner), so the summation order is the unit order.
+    rc = hip_rc(run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0));
+    if (rc != SLIMATTN_OK) return rc;
+    if (per_unit) {
+      rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));
+      if (rc != SLIMATTN_OK) return rc;
+    }
+  }
+  if (hi == n_units) {
+    rc = hip_rc(f32 ? launch_finalize_f32(ctx, acc_dk, acc_dv, (float*)dK, (float*)dV)
+                    : launch_finalize_bf16(ctx, acc_dk, acc_dv, dK, dV));
+  }
+  return rc;
+}
+
+}  // extern "C"

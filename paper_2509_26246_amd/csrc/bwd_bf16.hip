@@ -1,0 +1,375 @@
+// Backward, bf16 inputs, MFMA products with fp32 accumulation.
+//
+// The scores are recomputed from q, k and the saved lse (paper, Asymmetric Cost Profile: the
+// backward of memory-efficient attention re-does the score product, which is why it costs 2.5x
+// the forward).  Two kernels:
+//   dQ    : a block owns 128 query rows of one head and walks the keys it can see;
+//           S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T.
+//   dK/dV : a block owns 128 key rows of one KV head and walks every query row of the launch
+//           scope at or after them, for every query head of the group, in a fixed order;
+//           S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.  A key tile's gradient is thus
+//           summed by its single owner (the paper's "KV gradients from subsequent slices"),
+//           with no float atomics; across launches the owner continues from fp32 accumulators.
+// In both, the lane layout of the first products' accumulators is, unchanged, the B operand of
+// the last products; the matching A operands (K^T, dO^T, Q^T) come from LDS transpose loads.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "mfma_utils.h"
+
+namespace slimattn {
+namespace {
+
+constexpr int kDqBQ = 128, kDqBK = 64;
+constexpr int kKvOwn = 128, kQStep = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dO,
+                                                         float* __restrict__ delta, int T, int Hq) {
+  constexpr int LPR = D / 8;                                   // lanes per (row, head)
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t rh = idx / LPR;                                // row * Hq + head
+  const bool live = rh < (int64_t)T * Hq;
+  float s = 0.f;
+  if (live) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + idx * 8);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + idx * 8);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s = fmaf((float)a[t], (float)b[t], s);
+  }
+#pragma unroll
+  for (int w = LPR / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w);
+  if (live && (idx % LPR) == 0) delta[(size_t)(rh % Hq) * T + (rh / Hq)] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                         const bf16* __restrict__ v, const bf16* __restrict__ dO,
+                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         bf16* __restrict__ dQ, const QItem* __restrict__ items, int n_items,
+                                                         int T, int Hq, int Hkv, float scale) {
+  constexpr int NKS = D / 16, NDB = D / 32;
+  constexpr int kTileBytes = kDqBK * D * 2;
+  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];
+
+  const int g = Hq / Hkv;
+  int item_idx, hk, hg;
+  if (!map_block(blockIdx.x, g, Hkv, n_items, &item_idx, &hk, &hg)) return;
+  const int h = hk * g + hg;
+  const QItem it = items[item_idx];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int q0w = it.q_row0 + 32 * wave, my_row = q0w + l32, q_end = it.q_row0 + it.q_rows;
+  const int ld_row = min(my_row, T - 1);
+
+  bf16x8 qf[NKS], dof[NKS];
+  {
+    const size_t off = ((size_t)ld_row * Hq + h) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + 16 * ks);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * ks);
+    }
+  }
+  const float lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
+  const float dlt = delta[(size_t)h * T + ld_row];
+  const float c2 = scale * kLog2e;
+  floatx16 acc[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+  TileStage<D, kDqBK, 256> stK, stV;
+  const int n_tiles = (q_end - it.kv_start + kDqBK - 1) / kDqBK;
+  stK.load(k, it.kv_start, Hkv, hk, T, tid);
+  stV.load(v, it.kv_start, Hkv, hk, T, tid);
+  stK.store(smem[0][0], tid);
+  stV.store(smem[0][1], tid);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = it.kv_start + t * kDqBK;
+    const char* tK = smem[t & 1][0];
+    const char* tV = smem[t & 1][1];
+    stK.load(k, j0 + kDqBK, Hkv, hk, T, tid);      // next tile (clamped rows past the end; unused then)
+    stV.load(v, j0 + kDqBK, Hkv, hk, T, tid);
+    if (j0 <= q0w + 31) {
+      bf16x8 dsf[4];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        floatx16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          s = mfma32(lds_frag_row<D>(tK, 32 * b + l32, 16 * ks + 8 * half), qf[ks], s);
+          dp = mfma32(lds_frag_row<D>(tV, 32 * b + l32, 16 * ks + 8 * half), dof[ks], dp);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
+          s[r] = (key <= my_row) ? p * (dp[r] - dlt) : 0.f;
+        }
+        dsf[2 * b] = pack8(s, 0);
+        dsf[2 * b + 1] = pack8(s, 8);
+      }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int ks2 = 0; ks2 < 4; ++ks2)
+          acc[db] = mfma32(lds_frag_tr<D>(tK, 16 * ks2, 32 * db, lane), dsf[ks2], acc[db]);
+    }
+    if (t + 1 < n_tiles) {
+      stK.store(smem[(t + 1) & 1][0], tid);
+      stV.store(smem[(t + 1) & 1][1], tid);
+    }
+    __syncthreads();
+  }
+  if (my_row < q_end) {
+    bf16* out = dQ + ((size_t)my_row * Hq + h) * D;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        bf16x4 w;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) w[x] = (bf16)(acc[db][4 * gq + x] * scale);
+        *reinterpret_cast<bf16x4*>(out + 32 * db + 8 * gq + 4 * half) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                           const bf16* __restrict__ v, const bf16* __restrict__ dO,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           float* __restrict__ acc_dk, float* __restrict__ acc_dv,
+                                                           bf16* __restrict__ dK, bf16* __restrict__ dV,
+                                                           const KvItem* __restrict__ items, int n_items,
+                                                           const Seg* __restrict__ segs, int T, int Hq, int Hkv, float scale,
+                                                           int load_acc, int store_final) {
+  constexpr int NKS = D / 16, NDB = D / 32;
+  constexpr int kTileBytes = kQStep * D * 2;
+  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];   // [buffer][Q, dO]
+  __shared__ __attribute__((aligned(16))) float s_lse[2][kQStep];
+  __shared__ __attribute__((aligned(16))) float s_delta[2][kQStep];
+
+  const int g = Hq / Hkv;
+  // one block per (key tile, kv head); kv heads of one tile adjacent, heavy tiles first
+  const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
+  if (item_idx >= n_items) return;
+  const KvItem it = items[item_idx];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int kv0w = it.kv_row0 + 32 * wave, my_key = kv0w + l32, kv_end = it.kv_row0 + it.kv_rows;
+  const int ld_key = min(my_key, T - 1);
+  const float c2 = scale * kLog2e;
+
+  bf16x8 kf[NKS], vf[NKS];
+  {
+    const size_t off = ((size_t)ld_key * Hkv + hk) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + 16 * ks);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
+    }
+  }
+  floatx16 dk[NDB], dv[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
+
+  // Flattened walk: for each run, for each head of the group, for each 64-row step.
+  int sgi = it.seg_begin, hh = 0;
+  Seg sg = segs[sgi];
+  int i0 = max(sg.q_lo, it.kv_row0);
+  bool have = true;                                   // a key tile always has at least its own rows
+  TileStage<D, kQStep, 256> stQ, stDO;
+  float pre_lse = 0.f, pre_delta = 0.f;
+#define SLIMATTN_FETCH(row0_, head_)                                   \
+  do {                                                                 \
+    stQ.load(q, (row0_), Hq, (head_), T, tid);                         \
+    stDO.load(dO, (row0_), Hq, (head_), T, tid);                       \
+    const int r_ = min((row0_) + (tid & (kQStep - 1)), T - 1);         \
+    pre_lse = lse[(size_t)(head_) * T + r_] * kLog2e;                  \
+    pre_delta = delta[(size_t)(head_) * T + r_];                       \
+  } while (0)
+#define SLIMATTN_COMMIT(buf_)                                          \
+  do {                                                                 \
+    stQ.store(smem[(buf_)][0], tid);                                   \
+    stDO.store(smem[(buf_)][1], tid);                                  \
+    if (tid < kQStep) { s_lse[(buf_)][tid] = pre_lse; s_delta[(buf_)][tid] = pre_delta; } \
+  } while (0)
+  SLIMATTN_FETCH(i0, hk * g + hh);
+  SLIMATTN_COMMIT(0);
+  __syncthreads();
+
+  int buf = 0;
+  while (have) {
+    const int cur_i0 = i0, cur_hi = sg.q_hi;
+    // advance to the next step (uniform across the block)
+    i0 += kQStep;
+    if (i0 >= sg.q_hi) {
+      if (++hh == g) {
+        hh = 0;
+        if (++sgi == it.seg_end) have = false; else sg = segs[sgi];
+      }
+      if (have) i0 = max(sg.q_lo, it.kv_row0);
+    }
+    SLIMATTN_FETCH(i0, hk * g + hh);                  // after the last step: clamped rows, never committed
+
+    if (cur_i0 + kQStep - 1 >= kv0w) {                // some query row of the step is at or after some key of the wave
+      const char* tQ = smem[buf][0];
+      const char* tDO = smem[buf][1];
+      const bool need_mask = (cur_i0 < kv0w + 31) || (cur_i0 + kQStep > cur_hi);
+#pragma unroll
+      for (int qb = 0; qb < kQStep / 32; ++qb) {
+        floatx16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          s = mfma32(lds_frag_row<D>(tQ, 32 * qb + l32, 16 * ks + 8 * half), kf[ks], s);
+          dp = mfma32(lds_frag_row<D>(tDO, 32 * qb + l32, 16 * ks + 8 * half), vf[ks], dp);
+        }
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int rl = 32 * qb + 8 * gq + 4 * half;            // local row of register 4*gq
+          const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[buf][rl]);
+          const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[buf][rl]);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const int r = 4 * gq + x;
+            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -l4[x]));
+            if (need_mask) {
+              const int qrow = cur_i0 + rl + x;
+              if (qrow < my_key || qrow >= cur_hi) p = 0.f;
+            }
+            s[r] = p;
+            dp[r] = p * (dp[r] - d4[x]);
+          }
+        }
+        const bf16x8 pf0 = pack8(s, 0), pf1 = pack8(s, 8), dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          dv[db] = mfma32(lds_frag_tr<D>(tDO, 32 * qb, 32 * db, lane), pf0, dv[db]);
+          dv[db] = mfma32(lds_frag_tr<D>(tDO, 32 * qb + 16, 32 * db, lane), pf1, dv[db]);
+          dk[db] = mfma32(lds_frag_tr<D>(tQ, 32 * qb, 32 * db, lane), dsf0, dk[db]);
+          dk[db] = mfma32(lds_frag_tr<D>(tQ, 32 * qb + 16, 32 * db, lane), dsf1, dk[db]);
+        }
+      }
+    }
+    if (have) SLIMATTN_COMMIT(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  if (my_key < kv_end) {
+    const size_t base = ((size_t)my_key * Hkv + hk) * D;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const size_t off = base + 32 * db + 8 * gq + 4 * half;
+        floatx4 a, b;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) { a[x] = dk[db][4 * gq + x] * scale; b[x] = dv[db][4 * gq + x]; }
+        if (load_acc) {
+          const floatx4 pa = *reinterpret_cast<const floatx4*>(acc_dk + off);
+          const floatx4 pb = *reinterpret_cast<const floatx4*>(acc_dv + off);
+          a += pa;
+          b += pb;
+        }
+        if (store_final) {
+          bf16x4 wa, wb;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) { wa[x] = (bf16)a[x]; wb[x] = (bf16)b[x]; }
+          *reinterpret_cast<bf16x4*>(dK + off) = wa;
+          *reinterpret_cast<bf16x4*>(dV + off) = wb;
+        } else {
+          *reinterpret_cast<floatx4*>(acc_dk + off) = a;
+          *reinterpret_cast<floatx4*>(acc_dv + off) = b;
+        }
+      }
+  }
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ a, bf16* __restrict__ b, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const floatx4 x = reinterpret_cast<const floatx4*>(a)[i];
+  bf16x4 w;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) w[t] = (bf16)x[t];
+  reinterpret_cast<bf16x4*>(b)[i] = w;
+}
+
+}  // namespace
+
+int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
+int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kKvOwn; }
+
+int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, float* delta) {
+  const slimattn_params& p = *c.p;
+  const int64_t n = c.T * p.n_q_heads * (p.head_dim / 8);
+  if (n == 0) return 0;
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(delta_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, delta,
+                       (int)c.T, p.n_q_heads);
+  else
+    hipLaunchKernelGGL(delta_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, delta,
+                       (int)c.T, p.n_q_heads);
+  return (int)hipGetLastError();
+}
+
+int launch_bwd_dq_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                       const float* delta, void* dQ, const QItem* items, int n_items) {
+  if (n_items == 0) return 0;
+  const slimattn_params& p = *c.p;
+  const int g = p.n_q_heads / p.n_kv_heads;
+  const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(dq_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, lse, delta, (bf16*)dQ, items, n_items, (int)c.T, p.n_q_heads,
+                       p.n_kv_heads, p.scale);
+  else
+    hipLaunchKernelGGL(dq_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, lse, delta, (bf16*)dQ, items, n_items, (int)c.T, p.n_q_heads,
+                       p.n_kv_heads, p.scale);
+  return (int)hipGetLastError();
+}
+
+int launch_bwd_dkdv_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                         const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
+                         int n_items, const Seg* segs, int load_acc, int store_final) {
+  if (n_items == 0) return 0;
+  const slimattn_params& p = *c.p;
+  const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(dkdv_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final);
+  else
+    hipLaunchKernelGGL(dkdv_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final);
+  return (int)hipGetLastError();
+}
+
+int launch_finalize_bf16(const LaunchCtx& c, const float* acc_dk, const float* acc_dv, void* dK, void* dV) {
+  const slimattn_params& p = *c.p;
+  const int64_t n4 = c.T * p.n_kv_heads * p.head_dim / 4;
+  if (n4 == 0) return 0;
+  const dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
+  hipLaunchKernelGGL(cast_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, acc_dk, (bf16*)dK, n4);
+  hipLaunchKernelGGL(cast_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, acc_dv, (bf16*)dV, n4);
+  return (int)hipGetLastError();
+}
+
+}  // namespace slimattn

@@ -1,0 +1,171 @@
+// Forward, bf16 inputs, MFMA products with fp32 accumulation, fp32 online softmax.
+//
+// What it computes (paper: PackFlow section -- a slice's queries attend to the cached keys and
+// values of every earlier slice of the sample and causally to the slice itself): for a query tile
+// of 128 rows of one head, walk the sample's keys kv_start .. last row in tiles of 64, keep a
+// running row maximum and row sum, and accumulate O.
+//
+// Shape of the computation on CDNA4: the block's 4 waves own 32 query rows each.  Scores are
+// produced transposed, S^T = K Q^T (A = K rows from LDS, B = Q held in registers), so that every
+// lane owns one query row: row max / row sum need one cross-lane exchange per tile and the
+// accumulator registers of S^T are, as they stand, the B operand of O^T += V^T P^T.  V^T is read
+// from the row-major V tile with LDS transpose loads.  K and V tiles are double-buffered in LDS;
+// the next tile's global loads are in flight while the current tile is multiplied.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "mfma_utils.h"
+
+namespace slimattn {
+namespace {
+
+constexpr int kFwdBQ = 128;   // query rows per block
+constexpr int kFwdBK = 64;    // keys per step
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                          const bf16* __restrict__ v, bf16* __restrict__ o,
+                                                          float* __restrict__ lse, const QItem* __restrict__ items,
+                                                          int n_items, int T, int Hq, int Hkv, float scale) {
+  constexpr int NKS = D / 16;   // contraction steps over the head dimension
+  constexpr int NDB = D / 32;   // 32-wide blocks of the head dimension
+  constexpr int kTileBytes = kFwdBK * D * 2;
+  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];   // [buffer][K, V]
+
+  const int g = Hq / Hkv;
+  int item_idx, hk, hg;
+  if (!map_block(blockIdx.x, g, Hkv, n_items, &item_idx, &hk, &hg)) return;
+  const int h = hk * g + hg;
+  const QItem it = items[item_idx];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int q0w = it.q_row0 + 32 * wave;          // first query row of this wave
+  const int my_row = q0w + l32;                   // the query row this lane owns
+  const int q_end = it.q_row0 + it.q_rows;
+
+  bf16x8 qf[NKS];
+  {
+    const bf16* qp = q + ((size_t)min(my_row, T - 1) * Hq + h) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  }
+  floatx16 oacc[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;           // running max (raw q.k units) and this lane's partial row sum
+  const float c2 = scale * kLog2e;
+
+  TileStage<D, kFwdBK, 256> stK, stV;
+  const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
+  stK.load(k, it.kv_start, Hkv, hk, T, tid);
+  stV.load(v, it.kv_start, Hkv, hk, T, tid);
+  stK.store(smem[0][0], tid);
+  stV.store(smem[0][1], tid);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = it.kv_start + t * kFwdBK;
+    const char* tK = smem[t & 1][0];
+    const char* tV = smem[t & 1][1];
+    const bool more = t + 1 < n_tiles;
+    stK.load(k, j0 + kFwdBK, Hkv, hk, T, tid);     // past the last tile this reads clamped rows; unused
+    stV.load(v, j0 + kFwdBK, Hkv, hk, T, tid);
+    if (j0 <= q0w + 31) {                          // wave-uniform: some key of the tile is visible to some row
+      floatx16 sacc[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+          sacc[b] = mfma32(lds_frag_row<D>(tK, 32 * b + l32, 16 * ks + 8 * half), qf[ks], sacc[b]);
+      }
+      if (j0 + kFwdBK - 1 > q0w) {                 // tile crosses the diagonal of this wave's rows
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key > my_row) sacc[b][r] = -INFINITY;
+          }
+      }
+      float tmax = sacc[0][0];
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
+      tmax = fmaxf(tmax, xor32(tmax));
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+      const float mc = m_new * c2;
+      float psum = 0.f;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], c2, -mc));
+          sacc[b][r] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int ks2 = 0; ks2 < 4; ++ks2) pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int ks2 = 0; ks2 < 4; ++ks2)
+          oacc[db] = mfma32(lds_frag_tr<D>(tV, 16 * ks2, 32 * db, lane), pf[ks2], oacc[db]);
+    }
+    if (more) {
+      stK.store(smem[(t + 1) & 1][0], tid);
+      stV.store(smem[(t + 1) & 1][1], tid);
+    }
+    __syncthreads();
+  }
+
+  const float l_tot = l_run + xor32(l_run);
+  if (my_row < q_end) {
+    const float inv = 1.f / l_tot;
+    bf16* op = o + ((size_t)my_row * Hq + h) * D;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        bf16x4 w;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) w[x] = (bf16)(oacc[db][4 * gq + x] * inv);
+        *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq + 4 * half) = w;
+      }
+    if (half == 0) lse[(size_t)h * T + my_row] = m_run * scale + __builtin_amdgcn_logf(l_tot) * kLn2;
+  }
+}
+
+}  // namespace
+
+int fwd_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kFwdBQ; }
+
+int launch_fwd_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, void* o, float* lse,
+                    const QItem* items, int n_items) {
+  if (n_items == 0) return 0;
+  const slimattn_params& p = *c.p;
+  const int g = p.n_q_heads / p.n_kv_heads;
+  const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(fwd_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (bf16*)o, lse, items, n_items, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale);
+  else
+    hipLaunchKernelGGL(fwd_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (bf16*)o, lse, items, n_items, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale);
+  return (int)hipGetLastError();
+}
+
+}  // namespace slimattn

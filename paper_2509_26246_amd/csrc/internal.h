@@ -1,0 +1,96 @@
+// Private declarations shared by the host builder, the table handle and the kernel launchers.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/slimattn.h"
+
+namespace slimattn {
+
+// Tile sizes for which work-lists are derived (query-tile rows / key-tile rows).
+constexpr int kNumTileSizes = 4;
+constexpr int kTileSizes[kNumTileSizes] = {32, 64, 128, 256};
+inline int tile_index(int rows) {
+  for (int i = 0; i < kNumTileSizes; ++i) if (kTileSizes[i] == rows) return i;
+  return -1;
+}
+
+// A query tile: rows [q_row0, q_row0 + q_rows) of one sample whose first token is kv_start.
+// Row i sees keys kv_start .. i.  The tile therefore needs keys [kv_start, q_row0 + q_rows).
+struct QItem { int32_t q_row0, q_rows, kv_start, pad; };
+
+// A run of query rows [q_lo, q_hi) of one sample that belong to the launch scope.
+struct Seg { int32_t q_lo, q_hi; };
+
+// A key tile: rows [kv_row0, kv_row0 + kv_rows) of one sample, and the scope's query runs of that
+// sample that end after kv_row0 (segs[seg_begin .. seg_end), ascending).
+struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end; };
+
+// A launch scope is either one unit or the whole list ("fused").  Its items are stored heavy-first.
+struct ScopeLists {
+  std::vector<int32_t> q_off[kNumTileSizes];    // per-unit offsets into q_items (size n_units + 1)
+  std::vector<QItem> q_items[kNumTileSizes];    // unit-major, each unit heavy-first
+  std::vector<int32_t> kv_off[kNumTileSizes];
+  std::vector<KvItem> kv_items[kNumTileSizes];
+  std::vector<Seg> segs;                        // all units' runs, referenced by kv_items
+};
+
+struct DeviceLists {                            // device mirrors (pointers into one allocation)
+  const QItem* q_items[kNumTileSizes];
+  const KvItem* kv_items[kNumTileSizes];
+  const Seg* segs;
+};
+
+}  // namespace slimattn
+
+struct slimattn_tables {
+  int32_t n_samples = 0, n_slices = 0, n_units[2] = {0, 0};
+  int64_t total_tokens = 0;
+  std::vector<int32_t> cu;
+  std::vector<slimattn_slice> slices;
+  std::vector<int32_t> unit_ptr[2], unit_slices[2];      // [0] forward list, [1] backward list
+  slimattn::ScopeLists per_unit[2];                       // one scope per unit of each list
+  slimattn::ScopeLists fused;                             // one scope: every slice (same for both passes)
+  slimattn::DeviceLists d_per_unit[2], d_fused;
+  const int32_t* d_cu = nullptr;
+  const slimattn_slice* d_slices = nullptr;
+  void* d_blob = nullptr;
+  int device = -1;
+};
+
+namespace slimattn {
+
+struct LaunchCtx {
+  const slimattn_params* p;
+  void* stream;           // hipStream_t
+  int64_t T;
+};
+
+// Kernel launchers (defined in the .hip files).  Each returns a hipError_t as int.
+int launch_fwd_f32(const LaunchCtx&, const float* q, const float* k, const float* v, float* o, float* lse,
+                   const QItem* items, int n_items);
+int launch_bwd_delta_f32(const LaunchCtx&, const float* o, const float* dO, float* delta);
+int launch_bwd_dq_f32(const LaunchCtx&, const float* q, const float* k, const float* v, const float* dO, const float* lse,
+                      const float* delta, float* dQ, const QItem* items, int n_items);
+int launch_bwd_dkdv_f32(const LaunchCtx&, const float* q, const float* k, const float* v, const float* dO, const float* lse,
+                        const float* delta, float* acc_dk, float* acc_dv, float* dK, float* dV, const KvItem* items,
+                        int n_items, const Seg* segs, int load_acc, int store_final);
+int launch_finalize_f32(const LaunchCtx&, const float* acc_dk, const float* acc_dv, float* dK, float* dV);
+int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
+
+int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
+                    const QItem* items, int n_items);
+int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, float* delta);
+int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                       const float* delta, void* dQ, const QItem* items, int n_items);
+int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                         const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
+                         int n_items, const Seg* segs, int load_acc, int store_final);
+int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);
+
+// Tile sizes each kernel family uses (must be one of kTileSizes).
+int fwd_q_tile(int dtype, int head_dim);
+int dq_q_tile(int dtype, int head_dim);
+int dkdv_kv_tile(int dtype, int head_dim);
+
+}  // namespace slimattn

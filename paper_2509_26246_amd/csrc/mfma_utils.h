@@ -1,0 +1,120 @@
+// Device helpers for the bf16 MFMA kernels (gfx950): vector types, swizzled LDS tiles, fragment
+// reads in both orientations, global<->LDS staging.
+//
+// MFMA 32x32x16 bf16 operand layout (lane l, half = l / 32, n = l % 32):
+//   A[m = n][k = 8*half + t], B[k = 8*half + t][n], t = 0..7 (eight consecutive k per lane);
+//   C[i = 8*(r/4) + 4*half + (r%4)][j = n], r = 0..15.
+// A product's C registers r = 8e .. 8e+7 therefore hold, for a fixed column, the rows
+// {16e + 4*half + 0..3} and {16e + 8 + 4*half + 0..3}; used as the next product's B operand they
+// fix which row each k-slot stands for, and the A operand of that product is read to match
+// (transposed LDS reads below).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slimattn {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __bf16 bf16;
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+// Swizzled LDS tile of ROWS x D bf16 (no padding).  The 16-byte unit index is XORed with a
+// function of the row so that (a) 16 consecutive rows at one column and (b) 4 consecutive rows
+// x 4 consecutive units both touch 16 distinct units of a 256-byte bank line.
+template <int D>
+__device__ __forceinline__ int lds_off16(int row, int unit);
+template <>
+__device__ __forceinline__ int lds_off16<128>(int row, int unit) {
+  const int f = ((row & 3) << 2) | ((row >> 2) & 3);
+  return row * 256 + ((unit ^ f) << 4);
+}
+template <>
+__device__ __forceinline__ int lds_off16<64>(int row, int unit) {
+  const int R = row >> 1;
+  const int f = ((R & 1) << 2) | ((R >> 1) & 3);
+  const int u = ((row & 1) << 3) | unit;
+  return R * 256 + ((u ^ f) << 4);
+}
+
+// Row-major fragment: 8 consecutive columns (col0 multiple of 8) of one row.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_frag_row(const char* tile, int row, int col0) {
+  return *reinterpret_cast<const bf16x8*>(tile + lds_off16<D>(row, col0 >> 3));
+}
+
+// Transposed fragment for an A operand with m = column, k = row: lane l receives, for column
+// col0 + (l % 32), the rows {row0 + 4*half + 0..3} and {row0 + 8 + 4*half + 0..3}.
+// Built from two LDS transpose loads; in each, the 16 lanes of a group supply the addresses of
+// 4 rows x 4 chunks of 4 columns, and lane i gets column i of the four rows.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int row0, int col0, int lane) {
+  const int i = lane & 15, grp = lane >> 4;
+  const int row = row0 + 4 * (grp >> 1) + (i >> 2);
+  const int col = col0 + 16 * (grp & 1) + 4 * (i & 3);
+  const int off = lds_off16<D>(row, col >> 3) + ((col & 4) << 1);
+  const int off2 = lds_off16<D>(row + 8, col >> 3) + ((col & 4) << 1);
+  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(tile + off));
+  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(tile + off2));
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+  short8v r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Pack eight fp32 accumulators (registers r0 .. r0+7 of a C tile) into a bf16 B operand.
+__device__ __forceinline__ bf16x8 pack8(const floatx16& c, int r0) {
+  bf16x8 out;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) out[t] = (bf16)c[r0 + t];
+  return out;
+}
+
+// Stage ROWS x D bf16 rows [row0, row0+ROWS) of head h of a [T, H, D] tensor: global -> registers.
+// Rows past T-1 are clamped (their values are never used unmasked).
+template <int D, int ROWS, int NT>
+struct TileStage {
+  static constexpr int kChunks = ROWS * D / 8 / NT;     // 16-byte chunks per thread
+  static_assert(ROWS * D / 8 % NT == 0, "tile must divide evenly over the block");
+  uint4 r[kChunks];
+  __device__ __forceinline__ void load(const bf16* __restrict__ base, int row0, int H, int h, int T, int tid) {
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+      const int c = tid + NT * i, row = c / (D / 8), u = c % (D / 8);
+      const int gr = min(row0 + row, T - 1);
+      r[i] = *reinterpret_cast<const uint4*>(base + ((size_t)gr * H + h) * D + u * 8);
+    }
+  }
+  __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+      const int c = tid + NT * i, row = c / (D / 8), u = c % (D / 8);
+      *reinterpret_cast<uint4*>(tile + lds_off16<D>(row, u)) = r[i];
+    }
+  }
+};
+
+__device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32); }
+
+// Block -> (work item, kv head, head in group) so that the g query heads that share one K/V
+// stream run back to back on the same XCD (blocks are dealt round-robin over the 8 XCDs) and
+// heavy items come first on every XCD.  Returns false for padding blocks.
+__device__ __forceinline__ bool map_block(int block, int g, int Hkv, int n_items, int* item, int* hk, int* hg) {
+  const int xcd = block & 7, slot = block >> 3;
+  *hg = slot % g;
+  const int j = (slot / g) * 8 + xcd;
+  if (j >= n_items * Hkv) return false;
+  *item = j / Hkv;
+  *hk = j % Hkv;
+  return true;
+}
+inline int mapped_grid(int n_items, int Hkv, int g) { return ((n_items * Hkv + 7) / 8) * 8 * g; }
+
+}  // namespace slimattn

@@ -1,0 +1,205 @@
+// Table handle: validation, derived tile work-lists, device upload.
+//
+// The derived lists are private to the library.  A launch scope is one unit, or the whole list.
+// Inside a scope the slices of a sample that touch each other are merged into runs of query rows;
+// runs are cut into query tiles (forward, dQ) and the sample prefix they can see is cut into key
+// tiles (dK/dV: the tile's owner sums the contributions of every run that ends after it --
+// the paper's "backward pass depends on KV gradients from subsequent slices", DAG simulator
+// section).  Items are ordered heavy-first so that the hardware's in-order block dispatch acts
+// as a longest-processing-time schedule.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+
+namespace slimattn {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+// Runs of one scope: slices (any order) -> per sample, ascending, adjacent slices merged.
+struct Run { int32_t sample, q_lo, q_hi, kv_start; };
+
+std::vector<Run> merge_runs(const slimattn_slice* sl, const int32_t* ids, int32_t count) {
+  std::vector<Run> runs;
+  runs.reserve(count);
+  for (int32_t i = 0; i < count; ++i) {
+    const slimattn_slice& s = sl[ids[i]];
+    runs.push_back(Run{s.sample, s.q_start, s.q_start + s.q_len, s.kv_start});
+  }
+  std::sort(runs.begin(), runs.end(), [](const Run& a, const Run& b) { return a.q_lo < b.q_lo; });
+  std::vector<Run> out;
+  for (const Run& r : runs) {
+    if (!out.empty() && out.back().sample == r.sample && out.back().q_hi == r.q_lo) out.back().q_hi = r.q_hi;
+    else out.push_back(r);
+  }
+  return out;
+}
+
+void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
+  const int32_t seg_base = (int32_t)L.segs.size();
+  for (const Run& r : runs) L.segs.push_back(Seg{r.q_lo, r.q_hi});
+  for (int z = 0; z < kNumTileSizes; ++z) {
+    const int32_t B = kTileSizes[z];
+    // query tiles, heavy-first by visible prefix length
+    std::vector<QItem> qi;
+    for (const Run& r : runs)
+      for (int32_t a = r.q_lo; a < r.q_hi; a += B) qi.push_back(QItem{a, std::min(B, r.q_hi - a), r.kv_start, 0});
+    std::stable_sort(qi.begin(), qi.end(), [](const QItem& a, const QItem& b) {
+      return (a.q_row0 + a.q_rows - a.kv_start) > (b.q_row0 + b.q_rows - b.kv_start);
+    });
+    L.q_items[z].insert(L.q_items[z].end(), qi.begin(), qi.end());
+    L.q_off[z].push_back((int32_t)L.q_items[z].size());
+    // key tiles: per sample, prefix [kv_start, last run's end); heavy-first by query rows at or after the tile
+    std::vector<KvItem> ki;
+    std::vector<int64_t> weight;
+    size_t i = 0;
+    while (i < runs.size()) {
+      size_t j = i;
+      while (j < runs.size() && runs[j].sample == runs[i].sample) ++j;
+      const int32_t kv0 = runs[i].kv_start, kv_end = runs[j - 1].q_hi;
+      for (int32_t a = kv0; a < kv_end; a += B) {
+        size_t first = i;
+        while (runs[first].q_hi <= a) ++first;             // exists: the last run ends after a
+        int64_t rows = 0;
+        for (size_t r = first; r < j; ++r) rows += runs[r].q_hi - std::max(runs[r].q_lo, a);
+        ki.push_back(KvItem{a, std::min(B, kv_end - a), seg_base + (int32_t)first, seg_base + (int32_t)j});
+        weight.push_back(rows);
+      }
+      i = j;
+    }
+    std::vector<int32_t> order(ki.size());
+    for (size_t x = 0; x < order.size(); ++x) order[x] = (int32_t)x;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return weight[a] > weight[b]; });
+    for (int32_t x : order) L.kv_items[z].push_back(ki[x]);
+    L.kv_off[z].push_back((int32_t)L.kv_items[z].size());
+  }
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
+
+template <class T>
+size_t place(std::vector<char>& blob, const std::vector<T>& v) {
+  const size_t off = align_up(blob.size());
+  blob.resize(off + v.size() * sizeof(T));
+  if (!v.empty()) std::memcpy(blob.data() + off, v.data(), v.size() * sizeof(T));
+  return off;
+}
+
+}  // namespace
+
+int& last_hip_error() { return g_last_hip_error; }
+
+}  // namespace slimattn
+
+using namespace slimattn;
+
+extern "C" {
+
+int slimattn_last_hip_error(void) { return g_last_hip_error; }
+
+int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                           const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
+                           const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
+                           slimattn_tables** out) {
+  if (!out) return SLIMATTN_EINVAL;
+  *out = nullptr;
+  int rc = slimattn_validate(cu, n, slices, n_slices, fwd_unit_ptr, fwd_unit_slices, n_fwd_units, SLIMATTN_CHECK_FORWARD, nullptr);
+  if (rc != SLIMATTN_OK) return rc;
+  rc = slimattn_validate(cu, n, slices, n_slices, bwd_unit_ptr, bwd_unit_slices, n_bwd_units, SLIMATTN_CHECK_BACKWARD, nullptr);
+  if (rc != SLIMATTN_OK) return rc;
+  slimattn_tables* t = new (std::nothrow) slimattn_tables();
+  if (!t) return SLIMATTN_ENOMEM;
+  try {
+    t->n_samples = n;
+    t->n_slices = n_slices;
+    t->n_units[0] = n_fwd_units;
+    t->n_units[1] = n_bwd_units;
+    t->total_tokens = cu[n];
+    t->cu.assign(cu, cu + n + 1);
+    t->slices.assign(slices, slices + n_slices);
+    t->unit_ptr[0].assign(fwd_unit_ptr, fwd_unit_ptr + n_fwd_units + 1);
+    t->unit_slices[0].assign(fwd_unit_slices, fwd_unit_slices + n_slices);
+    t->unit_ptr[1].assign(bwd_unit_ptr, bwd_unit_ptr + n_bwd_units + 1);
+    t->unit_slices[1].assign(bwd_unit_slices, bwd_unit_slices + n_slices);
+    for (int pass = 0; pass < 2; ++pass) {
+      for (int z = 0; z < kNumTileSizes; ++z) { t->per_unit[pass].q_off[z].push_back(0); t->per_unit[pass].kv_off[z].push_back(0); }
+      for (int32_t u = 0; u < t->n_units[pass]; ++u) {
+        const int32_t a = t->unit_ptr[pass][u], b = t->unit_ptr[pass][u + 1];
+        append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a));
+      }
+    }
+    std::vector<int32_t> all(n_slices);
+    for (int32_t i = 0; i < n_slices; ++i) all[i] = i;
+    for (int z = 0; z < kNumTileSizes; ++z) { t->fused.q_off[z].push_back(0); t->fused.kv_off[z].push_back(0); }
+    append_scope(t->fused, merge_runs(slices, all.data(), n_slices));
+
+    // one blob, one upload
+    std::vector<char> blob;
+    const size_t off_cu = place(blob, t->cu), off_sl = place(blob, t->slices);
+    size_t off_q[3][kNumTileSizes], off_kv[3][kNumTileSizes], off_seg[3];
+    ScopeLists* lists[3] = {&t->per_unit[0], &t->per_unit[1], &t->fused};
+    for (int s = 0; s < 3; ++s) {
+      for (int z = 0; z < kNumTileSizes; ++z) {
+        off_q[s][z] = place(blob, lists[s]->q_items[z]);
+        off_kv[s][z] = place(blob, lists[s]->kv_items[z]);
+      }
+      off_seg[s] = place(blob, lists[s]->segs);
+    }
+    blob.resize(align_up(blob.size()) + 256);
+    hipError_t e = hipGetDevice(&t->device);
+    if (e == hipSuccess) e = hipMalloc(&t->d_blob, blob.size());
+    if (e == hipSuccess) e = hipMemcpy(t->d_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      if (t->d_blob) (void)hipFree(t->d_blob);
+      delete t;
+      return SLIMATTN_EHIP;
+    }
+    const char* base = (const char*)t->d_blob;
+    t->d_cu = (const int32_t*)(base + off_cu);
+    t->d_slices = (const slimattn_slice*)(base + off_sl);
+    DeviceLists* dl[3] = {&t->d_per_unit[0], &t->d_per_unit[1], &t->d_fused};
+    for (int s = 0; s < 3; ++s) {
+      for (int z = 0; z < kNumTileSizes; ++z) {
+        dl[s]->q_items[z] = (const QItem*)(base + off_q[s][z]);
+        dl[s]->kv_items[z] = (const KvItem*)(base + off_kv[s][z]);
+      }
+      dl[s]->segs = (const Seg*)(base + off_seg[s]);
+    }
+  } catch (const std::bad_alloc&) {
+    delete t;
+    return SLIMATTN_ENOMEM;
+  }
+  *out = t;
+  return SLIMATTN_OK;
+}
+
+void slimattn_tables_destroy(slimattn_tables* t) {
+  if (!t) return;
+  if (t->d_blob) (void)hipFree(t->d_blob);
+  delete t;
+}
+
+int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
+  if (!t) return -1;
+  switch (what) {
+    case 0: return t->total_tokens;
+    case 1: return t->n_samples;
+    case 2: return t->n_slices;
+    case 3: return t->n_units[0];
+    case 4: return t->n_units[1];
+    default: return -1;
+  }
+}
+
+size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_t hkv, int32_t d) {
+  if (!t || hq < 1 || hkv < 1 || d < 1) return 0;
+  const size_t T = (size_t)t->total_tokens;
+  return align_up(2 * T * hkv * d * sizeof(float)) + align_up(T * hq * sizeof(float)) + 256;
+}
+
+}  // extern "C"

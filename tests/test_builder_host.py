@@ -1,0 +1,137 @@
+"""Host-side builder of the C-ABI library against the independent table oracle: bit-exact.
+No GPU compute here; also checks that the library loads and exports what the header declares."""
+import ctypes
+import itertools
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_26246_amd as S
+import workloads as W
+from oracle import tables as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+POLICIES = [
+    ("ALL", {}), ("PER_SAMPLE", {}), ("PER_SAMPLE", {"backward": True}),
+    ("ROUND_ROBIN", {"m": 3}), ("ROUND_ROBIN", {"m": 4, "descending": True}),
+    ("PREFIX_FILL", {"m": 3, "w_quad": 2, "w_lin": 0, "backward": False}),
+    ("PREFIX_FILL", {"m": 7, "w_quad": 5, "w_lin": 106496, "backward": True}),
+    ("TOKEN_CAP", {"cap": 10, "backward": False}), ("TOKEN_CAP", {"cap": 3, "backward": True}),
+    ("SEEDED_LPT", {"w_quad": 2, "w_lin": 0}), ("SEEDED_LPT", {"w_quad": 2, "w_lin": 1, "m_min": 3}),
+    ("ISOLATE_FILL", {"m": 4, "w_quad": 5, "w_lin": 0, "theta_num": 1, "theta_den": 1, "backward": True}),
+    ("ISOLATE_FILL", {"m": 3, "w_quad": 2, "w_lin": 1, "theta_num": 1, "theta_den": 2, "backward": False}),
+]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "slimattn.h")).read()
+    declared = set(re.findall(r"\b(slimattn_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(S.EXPORTED_SYMBOLS)
+    lib = S.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert S.version() >= 100 and S.strerror(-2) == "inconsistent tables"
+
+
+def test_golden_cfg0_tables_from_native_builder():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "cfg0_tables.json")))
+    cu, sl = S.build_slices(g["lengths"], g["slice_size"])
+    assert cu.tolist() == g["cu"] and sl.tolist() == g["slices"]
+    w = W.WORKLOADS["cfg0_tiny_f32"]
+    up, us = S.build_units(cu, sl, w.fwd_policy[0], **w.fwd_policy[1])
+    assert up.tolist() == g["fwd_unit_ptr"] and us.tolist() == g["fwd_unit_slices"]
+    up, us = S.build_units(cu, sl, w.bwd_policy[0], **w.bwd_policy[1])
+    assert up.tolist() == g["bwd_unit_ptr"] and us.tolist() == g["bwd_unit_slices"]
+    assert sum(S.slice_pairs(r) for r in sl) == g["pairs_total"]
+
+
+@pytest.mark.parametrize("policy,params", POLICIES)
+def test_native_policies_bit_exact_vs_oracle(policy, params):
+    r = np.random.default_rng(7)
+    cases = [([5], 2), ([1, 1, 1], 1), ([9, 2, 14, 3], 4), ([4, 4, 4, 4, 4], 8), ([0, 3, 0], 2)]
+    for _ in range(25):
+        cases.append((r.integers(1, 300, size=r.integers(1, 20)).tolist(), int(r.integers(1, 70))))
+    for lengths, ssz in cases:
+        cu_o, sl_o = T.build_slices(lengths, ssz)
+        cu_n, sl_n = S.build_slices(lengths, ssz)
+        assert np.array_equal(cu_o, cu_n) and np.array_equal(sl_o, sl_n)
+        up_o, us_o = T.build_units(cu_o, sl_o, policy, **params)
+        up_n, us_n = S.build_units(cu_n, sl_n, policy, **params)
+        assert np.array_equal(up_o, up_n) and np.array_equal(us_o, us_n), (lengths, ssz)
+        assert S.validate(cu_n, sl_n, up_n, us_n)[0] == 0
+
+
+def test_native_tables_bit_exact_on_every_workload_and_seed():
+    for name, w in W.WORKLOADS.items():
+        for seed in W.SEEDS:
+            L = W.draw_lengths(w, np.random.default_rng(seed))
+            cu_o, sl_o = T.build_slices(L, w.slice_size)
+            cu_n, sl_n = S.build_slices(L, w.slice_size)
+            assert np.array_equal(cu_o, cu_n) and np.array_equal(sl_o, sl_n)
+            for backward, (pol, p) in ((False, w.fwd_policy), (True, w.bwd_policy)):
+                up_o, us_o = T.build_units(cu_o, sl_o, pol, **p)
+                up_n, us_n = S.build_units(cu_n, sl_n, pol, **p)
+                assert np.array_equal(up_o, up_n) and np.array_equal(us_o, us_n), (name, seed, pol)
+                mode = S.CHECK_BACKWARD if backward else S.CHECK_FORWARD
+                assert S.validate(cu_n, sl_n, up_n, us_n, mode)[0] == 0
+                if pol != "ROUND_ROBIN":
+                    assert S.validate(cu_n, sl_n, up_n, us_n, mode | S.CHECK_ORDER) == (0, "")
+
+
+def test_slices_from_bounds_and_pairs_and_flops():
+    lengths, bounds = [29, 11, 0, 4], [[1, 2, 20], [10], [], []]
+    cu_o, sl_o = T.build_slices_from_bounds(lengths, bounds)
+    cu_n, sl_n = S.build_slices_from_bounds(lengths, bounds)
+    assert np.array_equal(cu_o, cu_n) and np.array_equal(sl_o, sl_n)
+    for rec in sl_n:
+        assert S.slice_pairs(rec) == T.pairs_of_slice(rec)
+    assert S.flops_fwd(159875, 64, 2) == T.flops_fwd(159875, 64, 2) == 4 * 64 * 2 * 159875
+    assert 2 * S.flops_bwd(12345, 128, 32) == 5 * S.flops_fwd(12345, 128, 32)   # the paper's 1 : 2.5
+
+
+def test_native_validator_agrees_with_oracle_on_planted_faults():
+    cu, sl = S.build_slices([10, 6], 4)
+    up, us = S.build_units(cu, sl, "PER_SAMPLE")
+
+    def both(cu_, sl_, up_, us_):
+        rc, rule = S.validate(cu_, sl_, up_, us_)
+        ref = T.check_structure(cu_, sl_, up_, us_)
+        assert (rc == 0) == (ref == []), (rule, ref)
+        return rule
+
+    assert both(cu, sl, up, us) == ""
+    for row, col, delta in itertools.product(range(len(sl)), range(6), (-1, 1)):
+        bad = sl.copy(); bad[row, col] += delta
+        assert both(cu, bad, up, us) != ""
+    dup = us.copy(); dup[0] = dup[1]
+    assert both(cu, sl, up, dup) == "coverage"
+    oob = us.copy(); oob[0] = 99
+    assert both(cu, sl, up, oob) == "slice_range"
+    assert both(cu, sl, np.array([0, 2, 1, 5], np.int32), us) != ""
+    # order rules: only with the opt-in flag
+    rev = us[::-1].copy()
+    assert S.validate(cu, sl, up, rev, S.CHECK_FORWARD)[0] == 0
+    assert S.validate(cu, sl, up, rev, S.CHECK_FORWARD | S.CHECK_ORDER)[0] == -2
+    assert (S.validate(cu, sl, up, rev, S.CHECK_FORWARD | S.CHECK_ORDER)[0] == 0) == \
+        (T.check_order(sl, up, rev, False) == [])
+    upb, usb = S.build_units(cu, sl, "PER_SAMPLE", backward=True)
+    assert S.validate(cu, sl, upb, usb, S.CHECK_BACKWARD | S.CHECK_ORDER)[0] == 0
+    assert S.validate(cu, sl, upb, usb, S.CHECK_FORWARD | S.CHECK_ORDER)[0] == -2
+
+
+def test_error_codes():
+    lib = S.load_library()
+    n = ctypes.c_int32(0)
+    L = np.array([5, -1], np.int32)
+    cu = np.zeros(3, np.int32)
+    p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    assert lib.slimattn_build_slices(p(L), 2, 4, p(cu), None, 0, ctypes.byref(n)) == -1       # negative length
+    L = np.array([5, 9], np.int32)
+    assert lib.slimattn_build_slices(p(L), 2, 0, p(cu), None, 0, ctypes.byref(n)) == -1       # slice size 0
+    assert lib.slimattn_build_slices(p(L), 2, 4, p(cu), None, 0, ctypes.byref(n)) == -3 and n.value == 5
+    with pytest.raises(S.SlimAttnError):
+        S.build_units(cu, np.zeros((1, 8), np.int32), "PREFIX_FILL", m=0, w_quad=1)

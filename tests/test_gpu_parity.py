@@ -1,0 +1,196 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
+seeded inputs.  Tolerances (max-abs vs fp64): fp32 mode 1e-5; bf16 mode 2e-2 on O and 5e-2 on
+dQ/dK/dV (inputs are bf16-exact, so the error measured is the kernels')."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_26246_amd as S
+import workloads as W
+from oracle import attention as A
+from paper_2509_26246_amd import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_O, TOL_G = 2e-2, 5e-2
+
+
+def _draw(T_, hq, hkv, d, seed, bf16, qs=1.0, dos=1.0):
+    r = np.random.default_rng(seed)
+    arrs = [r.standard_normal((T_, hq, d), dtype=np.float32) * np.float32(qs),
+            r.standard_normal((T_, hkv, d), dtype=np.float32) * np.float32(qs),
+            r.standard_normal((T_, hkv, d), dtype=np.float32) * np.float32(qs),
+            r.standard_normal((T_, hq, d), dtype=np.float32) * np.float32(dos)]
+    return [W.bf16_round(a) if bf16 else a for a in arrs]
+
+
+def _oracle(q, k, v, dO, cu, scale):
+    o, lse = A.fwd_packed(q, k, v, cu, scale)
+    dq, dk, dv = A.bwd_packed(q, k, v, o, lse, dO, cu, scale)
+    return o, lse, dq, dk, dv
+
+
+def _check(prob, ref, tol_o, tol_g, tag=""):
+    o, lse, dq, dk, dv = ref
+    got = {"o": H.device_to_f32(prob.o), "lse": prob.lse.cpu().numpy(), "dq": H.device_to_f32(prob.dQ),
+           "dk": H.device_to_f32(prob.dK), "dv": H.device_to_f32(prob.dV)}
+    want = {"o": o, "lse": lse, "dq": dq, "dk": dk, "dv": dv}
+    for name in ("o", "lse", "dq", "dk", "dv"):
+        err = float(np.max(np.abs(got[name].astype(np.float64) - want[name]))) if want[name].size else 0.0
+        tol = tol_o if name in ("o", "lse") else tol_g
+        assert err <= tol, f"{tag} {name}: max-abs {err:.3e} > {tol}"
+        assert np.isfinite(got[name]).all(), f"{tag} {name} not finite"
+
+
+def _poison(prob):
+    for t in (prob.o, prob.dQ, prob.dK, prob.dV):
+        t.fill_(float("nan"))
+    prob.lse.fill_(float("nan"))
+    prob.workspace.fill_(0xFF)
+
+
+def _run_modes(prob, ref, tol_o, tol_g, tag):
+    """Fused launch, one launch per unit, and the list split over two calls: all must match."""
+    nf, nb = prob.tables.n_fwd_units, prob.tables.n_bwd_units
+    _poison(prob)
+    prob.forward(); prob.backward(); torch.cuda.synchronize()
+    _check(prob, ref, tol_o, tol_g, tag + "/fused")
+    _poison(prob)
+    prob.forward(flags=S.FLAG_PER_UNIT_LAUNCH); prob.backward(flags=S.FLAG_PER_UNIT_LAUNCH); torch.cuda.synchronize()
+    _check(prob, ref, tol_o, tol_g, tag + "/per-unit")
+    _poison(prob)
+    cf, cb = nf // 2, nb // 2
+    prob.forward(unit_lo=0, unit_hi=cf); prob.forward(unit_lo=cf, unit_hi=nf)
+    prob.backward(unit_lo=0, unit_hi=cb); prob.backward(unit_lo=cb, unit_hi=nb); torch.cuda.synchronize()
+    _check(prob, ref, tol_o, tol_g, tag + "/split")
+
+
+def _tables(lengths, slice_size, fwd_pol, bwd_pol):
+    cu, sl = S.build_slices(lengths, slice_size)
+    return cu, sl, S.build_units(cu, sl, fwd_pol[0], **fwd_pol[1]), S.build_units(cu, sl, bwd_pol[0], **bwd_pol[1])
+
+
+def test_cfg0_tiny_pack_fp32():
+    w = W.WORKLOADS["cfg0_tiny_f32"]
+    for seed in W.SEEDS:
+        rng = np.random.default_rng(seed)
+        L = W.draw_lengths(w, rng)
+        q, k, v, dO = W.draw_values(w, int(L.sum()), rng)
+        cu, sl, fu, bu = _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
+        scale = 1.0 / np.sqrt(w.head_dim)
+        ref = _oracle(q, k, v, dO, cu, scale)
+        prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=False, scale=scale)
+        _run_modes(prob, ref, TOL_F32, TOL_F32, f"cfg0 seed {seed}")
+        # the single-unit variant gives the same result
+        one = S.build_units(cu, sl, "ALL")
+        prob1 = H.make_problem(q, k, v, dO, cu, sl, one, one, bf16=False, scale=scale)
+        _run_modes(prob1, ref, TOL_F32, TOL_F32, f"cfg0/ALL seed {seed}")
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 16), (3, 1, 32), (2, 2, 128)])
+def test_fp32_gqa_and_head_dims(hq, hkv, d):
+    L = [70, 1, 129, 5, 64]
+    cu, sl, fu, bu = _tables(L, 48, ("TOKEN_CAP", {"cap": 100}), ("PREFIX_FILL", {"m": 5, "w_quad": 5, "w_lin": 0, "backward": True}))
+    q, k, v, dO = _draw(sum(L), hq, hkv, d, 5, False)
+    scale = d ** -0.5          # the 1e-5 bound is stated for N(0,1) inputs at the usual 1/sqrt(d) scale
+    ref = _oracle(q, k, v, dO, cu, scale)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=False, scale=scale)
+    _run_modes(prob, ref, TOL_F32, TOL_F32, f"f32 {hq}/{hkv}/{d}")
+
+
+@pytest.mark.parametrize("hq,hkv,d,slice_size", [(4, 2, 128, 64), (2, 1, 64, 64), (8, 2, 128, 192), (4, 4, 64, 1000)])
+def test_bf16_small_packs_full_oracle(hq, hkv, d, slice_size):
+    L = [37, 128, 200, 511, 1, 1000, 0, 129]
+    cu, sl, fu, bu = _tables(L, slice_size, ("PREFIX_FILL", {"m": 4, "w_quad": 2, "w_lin": 0}),
+                             ("ROUND_ROBIN", {"m": 3, "descending": True}))
+    q, k, v, dO = _draw(sum(L), hq, hkv, d, 11, True, 0.5, 0.1)
+    scale = d ** -0.5
+    ref = _oracle(q, k, v, dO, cu, scale)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    _run_modes(prob, ref, TOL_O, TOL_G, f"bf16 {hq}/{hkv}/{d}/S{slice_size}")
+
+
+def test_bf16_unit_variance_inputs():
+    # N(0,1) inputs (larger scores, sharper softmax) still inside the stated tolerances
+    L = [300, 77]
+    cu, sl, fu, bu = _tables(L, 128, ("PER_SAMPLE", {}), ("PER_SAMPLE", {"backward": True}))
+    q, k, v, dO = _draw(sum(L), 4, 2, 128, 13, True, 1.0, 0.1)
+    ref = _oracle(q, k, v, dO, cu, 128 ** -0.5)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True)
+    _run_modes(prob, ref, TOL_O, TOL_G, "bf16 N(0,1)")
+
+
+def test_bitwise_repeatable_and_grouping_invariant():
+    L = [700, 130, 64]
+    q, k, v, dO = _draw(sum(L), 4, 1, 128, 17, True, 0.5, 0.1)
+    outs = []
+    for fpol, bpol in ((("ALL", {}), ("ALL", {})),
+                       (("TOKEN_CAP", {"cap": 128}), ("ROUND_ROBIN", {"m": 4, "descending": True}))):
+        cu, sl, fu, bu = _tables(L, 64, fpol, bpol)
+        prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True)
+        runs = []
+        for flags in (0, 0, S.FLAG_PER_UNIT_LAUNCH, S.FLAG_PER_UNIT_LAUNCH):
+            _poison(prob)
+            prob.forward(flags=flags); prob.backward(flags=flags); torch.cuda.synchronize()
+            runs.append([t.view(torch.int16).cpu().numpy().copy() for t in (prob.o, prob.dQ, prob.dK, prob.dV)])
+        for a, b in ((runs[0], runs[1]), (runs[2], runs[3])):          # same launch mode twice: bit-identical
+            assert all(np.array_equal(x, y) for x, y in zip(a, b))
+        outs.append([H.device_to_f32(t) for t in (prob.o, prob.dQ, prob.dK, prob.dV)])
+        # O and dQ do not depend on the grouping at all (each row is computed by one block, same order)
+        assert np.array_equal(runs[0][0], runs[2][0]) and np.array_equal(runs[0][1], runs[2][1])
+    for x, y in zip(outs[0], outs[1]):                                  # across groupings: to tolerance
+        assert float(np.max(np.abs(x - y))) <= TOL_G
+
+
+def test_cfg1_full_size_sampled_rows_and_identities():
+    w = W.WORKLOADS["cfg1_llama8b_32k"]
+    rng = np.random.default_rng(1)
+    L = W.draw_lengths(w, rng)
+    T_ = int(L.sum())
+    q, k, v, dO = W.draw_values(w, T_, rng)
+    cu, sl, fu, bu = _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
+    scale = w.head_dim ** -0.5
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    prob.forward(); prob.backward(); torch.cuda.synchronize()
+    o, lse = H.device_to_f32(prob.o), prob.lse.cpu().numpy()
+    dq, dk, dv = H.device_to_f32(prob.dQ), H.device_to_f32(prob.dK), H.device_to_f32(prob.dV)
+    r = np.random.default_rng(99)
+    rows = np.concatenate([r.integers(0, T_, 48), cu[:-1], cu[1:] - 1]).astype(np.int64)
+    heads = r.integers(0, w.n_q_heads, len(rows))
+    ro, rl = A.fwd_rows(q, k, v, cu, scale, rows, heads)
+    rdq = A.dq_rows(q, k, v, dO, cu, scale, rows, heads)
+    assert np.max(np.abs(o[rows, heads] - ro)) <= TOL_O and np.max(np.abs(lse[heads, rows] - rl)) <= TOL_O
+    assert np.max(np.abs(dq[rows, heads] - rdq)) <= TOL_G
+    s_long = int(np.argmax(L))
+    keys = np.unique(np.concatenate([[cu[s_long], cu[s_long + 1] - 1], r.integers(cu[s_long], cu[s_long + 1], 24)]))
+    for hk in (0, w.n_kv_heads - 1):
+        rdk, rdv = A.dkdv_rows(q, k, v, dO, cu, scale, s_long, hk, keys)
+        assert np.max(np.abs(dk[keys, hk] - rdk)) <= TOL_G and np.max(np.abs(dv[keys, hk] - rdv)) <= TOL_G
+    # conservation laws over the full tensors (no oracle needed)
+    g = w.n_q_heads // w.n_kv_heads
+    for s in range(len(L)):
+        a, b = int(cu[s]), int(cu[s + 1])
+        lhs = dv[a:b].astype(np.float64).sum(0)                                        # [Hkv, d]
+        rhs = dO[a:b].astype(np.float64).reshape(b - a, w.n_kv_heads, g, -1).sum((0, 2))
+        assert np.max(np.abs(lhs - rhs)) <= 0.02 * np.sqrt(b - a) + 0.05
+        qdq = (q[a:b].astype(np.float64) * dq[a:b]).reshape(b - a, w.n_kv_heads, g, -1).sum((0, 2, 3))
+        kdk = (k[a:b].astype(np.float64) * dk[a:b]).sum((0, 2))
+        assert np.max(np.abs(qdq - kdk)) <= 0.02 * np.sqrt(b - a) + 0.05
+
+
+def test_rejects_bad_arguments():
+    L = [64]
+    cu, sl, fu, bu = _tables(L, 64, ("ALL", {}), ("ALL", {}))
+    q, k, v, dO = _draw(64, 2, 2, 64, 1, True)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True)
+    for over in ({"head_dim": 96}, {"n_kv_heads": 3}, {"dtype": 7}, {"unit_lo": 2}, {"unit_hi": 5}):
+        with pytest.raises(S.SlimAttnError) as e:
+            prob.forward(**over)
+        assert e.value.code == -1
+    with pytest.raises(S.SlimAttnError):
+        S.fwd(prob.q.data_ptr() + 2, prob.k, prob.v, prob.tables, prob.o, prob.lse, n_q_heads=2, n_kv_heads=2,
+              head_dim=64, dtype=S.BF16, scale=0.125)
+    with pytest.raises(S.SlimAttnError) as e:
+        S.tables_create(cu, sl, fu[0], fu[1] + 5, bu[0], bu[1])          # slice index out of range
+    assert e.value.code == -2
