@@ -83,7 +83,7 @@ typedef struct slimattn_params {
   int32_t total_tokens;      /* T */
   int32_t n_q_heads;         /* Hq */
   int32_t n_kv_heads;        /* Hkv, divides Hq */
-  int32_t head_dim;          /* d: 64 or 128 (bf16); any multiple of 4 up to 128 (f32) */
+  int32_t head_dim;          /* d: 64 or 128 (bf16); 16, 32, 64 or 128 (f32) */
   int32_t dtype;             /* SLIMATTN_F32 or SLIMATTN_BF16 */
   float   scale;             /* softmax scale applied to q.k */
   int32_t unit_lo, unit_hi;  /* run units [unit_lo, unit_hi) of the pass's list; unit_hi = -1 means all */
@@ -178,6 +178,28 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
 int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* dO, const slimattn_tables* t, void* dQ, void* dK,
                  void* dV, void* workspace, void* stream);
+
+/* ---- measurement aid --------------------------------------------------------------------------- */
+
+/* Kernel classes reported by slimattn_profile_read. */
+#define SLIMATTN_K_FWD       0
+#define SLIMATTN_K_DELTA     1
+#define SLIMATTN_K_DQ        2
+#define SLIMATTN_K_DKDV      3
+#define SLIMATTN_K_FINALIZE  4
+#define SLIMATTN_K_FILL      5
+#define SLIMATTN_K_COUNT     6
+
+/* Per-kernel timing for benchmarks (the paper calibrates its simulator from such primitive
+ * measurements, Primitive Measurements and Search Space).  max_launches > 0: create that many
+ * HIP event pairs on the current device; from then on every kernel launch made by slimattn_fwd /
+ * slimattn_bwd is bracketed by two events recorded on the launch's own stream until the pool is
+ * used up.  max_launches == 0: stop and destroy the events.  Not thread-safe; one device. */
+int slimattn_profile_enable(int32_t max_launches);
+
+/* Waits for the recorded events, adds up elapsed milliseconds and launch counts per kernel class
+ * into ms[SLIMATTN_K_COUNT] and launches[SLIMATTN_K_COUNT] (HOST), and rewinds the pool. */
+int slimattn_profile_read(double* ms, int64_t* launches);
 
 const char* slimattn_strerror(int code);
 int slimattn_last_hip_error(void);       /* hipError_t of the last EHIP on this thread */

@@ -19,7 +19,9 @@ EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
     "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
-    "slimattn_bwd", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version"]
+    "slimattn_bwd", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
+    "slimattn_profile_read"]
+KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "finalize", "fill"]
 
 
 class SlimAttnError(RuntimeError):
@@ -75,6 +77,8 @@ def load_library():
     lib.slimattn_strerror.restype = C.c_char_p
     lib.slimattn_last_hip_error.restype = C.c_int
     lib.slimattn_version.restype = C.c_int
+    lib.slimattn_profile_enable.argtypes = [C.c_int32]
+    lib.slimattn_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -241,3 +245,19 @@ def bwd(q, k, v, o, lse, dO, tables: Tables, dQ, dK, dV, workspace, *, n_q_heads
     if rc != 0:
         extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
         raise SlimAttnError(rc, "slimattn_bwd", extra)
+
+
+def profile_enable(max_launches: int) -> None:
+    rc = load_library().slimattn_profile_enable(max_launches)
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_profile_enable")
+
+
+def profile_read():
+    """{kernel class: (total ms, launches)} since the last read."""
+    ms = (C.c_double * len(KERNEL_CLASSES))()
+    n = (C.c_int64 * len(KERNEL_CLASSES))()
+    rc = load_library().slimattn_profile_read(ms, n)
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_profile_read")
+    return {name: (ms[i], n[i]) for i, name in enumerate(KERNEL_CLASSES)}

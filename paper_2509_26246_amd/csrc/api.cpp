@@ -2,6 +2,8 @@
 // No device allocation and no synchronisation happens here.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "internal.h"
 
 namespace slimattn {
@@ -35,6 +37,26 @@ int hip_rc(int e) {
 
 size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Optional per-launch timing (slimattn_profile_enable).  Events are created up front; recording
+// an event allocates nothing.
+struct Profiler {
+  std::vector<hipEvent_t> start, stop;
+  std::vector<int> cls;
+  size_t used = 0;
+  bool on = false;
+} g_prof;
+
+template <class F>
+int timed(int cls, void* stream, F&& launch) {
+  if (!g_prof.on || g_prof.used >= g_prof.start.size()) return launch();
+  const size_t i = g_prof.used++;
+  g_prof.cls[i] = cls;
+  (void)hipEventRecord(g_prof.start[i], (hipStream_t)stream);
+  const int e = launch();
+  (void)hipEventRecord(g_prof.stop[i], (hipStream_t)stream);
+  return e;
+}
+
 }  // namespace
 }  // namespace slimattn
 
@@ -52,9 +74,11 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
   const int z = tile_index(fwd_q_tile(p->dtype, p->head_dim));
   const LaunchCtx ctx{p, stream, t->total_tokens};
   auto run = [&](const QItem* items, int n) -> int {
-    return p->dtype == SLIMATTN_F32
-               ? launch_fwd_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (float*)o, lse, items, n)
-               : launch_fwd_bf16(ctx, q, k, v, o, lse, items, n);
+    return timed(SLIMATTN_K_FWD, stream, [&] {
+      return p->dtype == SLIMATTN_F32
+                 ? launch_fwd_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (float*)o, lse, items, n)
+                 : launch_fwd_bf16(ctx, q, k, v, o, lse, items, n);
+    });
   };
   const bool whole = lo == 0 && hi == t->n_units[0];
   if (whole && !(p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH))
@@ -90,22 +114,29 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
 
   if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
-    rc = hip_rc(f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
-                    : launch_bwd_delta_bf16(ctx, o, dO, delta));
+    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
+      return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
+                 : launch_bwd_delta_bf16(ctx, o, dO, delta);
+    }));
     if (rc != SLIMATTN_OK) return rc;
   }
   const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
   const int zk = tile_index(dkdv_kv_tile(p->dtype, p->head_dim));
   auto run_dq = [&](const QItem* items, int n) -> int {
-    return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
-                                   (float*)dQ, items, n)
-               : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse, delta, dQ, items, n);
+    return timed(SLIMATTN_K_DQ, stream, [&] {
+      return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
+                                     (float*)dQ, items, n)
+                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse, delta, dQ, items, n);
+    });
   };
   auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {
-    return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
-                                     acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc, store_final)
-               : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
-                                      store_final);
+    return timed(SLIMATTN_K_DKDV, stream, [&] {
+      return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
+                                       delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
+                                       store_final)
+                 : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                                        store_final);
+    });
   };
 
   if (whole && !per_unit) {
@@ -119,7 +150,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   const auto& qoff = t->per_unit[1].q_off[zq];
   const auto& koff = t->per_unit[1].kv_off[zk];
   if (lo == 0) {
-    rc = hip_rc(launch_fill_zero(ctx, acc_dk, (int64_t)(2 * acc_elems)));
+    rc = hip_rc(timed(SLIMATTN_K_FILL, stream, [&] { return launch_fill_zero(ctx, acc_dk, (int64_t)(2 * acc_elems)); }));
     if (rc != SLIMATTN_OK) return rc;
   }
   if (!per_unit) {
@@ -138,10 +169,48 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     }
   }
   if (hi == n_units) {
-    rc = hip_rc(f32 ? launch_finalize_f32(ctx, acc_dk, acc_dv, (float*)dK, (float*)dV)
-                    : launch_finalize_bf16(ctx, acc_dk, acc_dv, dK, dV));
+    rc = hip_rc(timed(SLIMATTN_K_FINALIZE, stream, [&] {
+      return f32 ? launch_finalize_f32(ctx, acc_dk, acc_dv, (float*)dK, (float*)dV)
+                 : launch_finalize_bf16(ctx, acc_dk, acc_dv, dK, dV);
+    }));
   }
   return rc;
+}
+
+int slimattn_profile_enable(int32_t max_launches) {
+  for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+  g_prof.start.clear();
+  g_prof.stop.clear();
+  g_prof.cls.clear();
+  g_prof.used = 0;
+  g_prof.on = false;
+  if (max_launches <= 0) return SLIMATTN_OK;
+  g_prof.start.resize(max_launches);
+  g_prof.stop.resize(max_launches);
+  g_prof.cls.assign(max_launches, 0);
+  for (int32_t i = 0; i < max_launches; ++i) {
+    hipError_t e = hipEventCreate(&g_prof.start[i]);
+    if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
+    if (e != hipSuccess) return hip_rc((int)e);
+  }
+  g_prof.on = true;
+  return SLIMATTN_OK;
+}
+
+int slimattn_profile_read(double* ms, int64_t* launches) {
+  if (!ms || !launches) return SLIMATTN_EINVAL;
+  for (int c = 0; c < SLIMATTN_K_COUNT; ++c) { ms[c] = 0.0; launches[c] = 0; }
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, g_prof.start[i], g_prof.stop[i]);
+    if (e != hipSuccess) return hip_rc((int)e);
+    ms[g_prof.cls[i]] += t;
+    launches[g_prof.cls[i]]++;
+  }
+  g_prof.used = 0;
+  return SLIMATTN_OK;
 }
 
 }  // extern "C"
