@@ -45,6 +45,40 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
+// One 64-key tile of the dQ walk for this wave's 32 query rows.  MASKED tiles touch the diagonal.
+template <int D, bool MASKED>
+__device__ __forceinline__ void dq_tile(const char* tK, const char* tV, const bf16x8 (&qf)[D / 16],
+                                        const bf16x8 (&dof)[D / 16], floatx16 (&acc)[D / 32], float c2, float lse2,
+                                        float dlt, int rel, int lane) {
+  constexpr int NKS = D / 16, NDB = D / 32;
+  const int half = lane >> 5, l32 = lane & 31;
+  bf16x8 dsf[4];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    floatx16 sc, dpc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dpc[r] = 0.f; }
+    // S^T = K Q^T and dP^T = V dO^T for 32 keys: K and V fragments alternate in one stream
+    frag_pipeline<2 * NKS, 4, 1, 1>(
+        [&](int i) { return lds_frag_row<D>((i & 1) ? tV : tK, 32 * b + l32, 16 * (i >> 1) + 8 * half); },
+        [&](int i, bf16x8 f) {
+          if (i & 1) dpc = mfma32(f, dof[i >> 1], dpc);
+          else sc = mfma32(f, qf[i >> 1], sc);
+        });
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], c2, -lse2));
+      const float ds = p * (dpc[r] - dlt);
+      sc[r] = (MASKED && 32 * b + 8 * (r >> 2) + (r & 3) > rel) ? 0.f : ds;   // key > row contributes nothing
+    }
+    dsf[2 * b] = pack8(sc, 0);
+    dsf[2 * b + 1] = pack8(sc, 8);
+  }
+  // dQ^T += K^T dS^T, K^T fragments by LDS transpose loads
+  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_frag_tr<D>(tK, 16 * (i & 3), 32 * (i >> 2), lane); },
+                                  [&](int i, bf16x8 f) { acc[i >> 2] = mfma32(f, dsf[i & 3], acc[i >> 2]); });
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                          const bf16* __restrict__ v, const bf16* __restrict__ dO,
@@ -53,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
                                                          int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = D / 16, NDB = D / 32;
   constexpr int kTileBytes = kDqBK * D * 2;
-  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];
 
   const int g = Hq / Hkv;
   int item_idx, hk, hg;
@@ -63,6 +97,8 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int q0w = it.q_row0 + 32 * wave, my_row = q0w + l32, q_end = it.q_row0 + it.q_rows;
   const int ld_row = min(my_row, T - 1);
+  stage_tile_direct<D, kDqBK, 256>(smem[0][0], k, it.kv_start, Hkv, hk, T, tid);
+  stage_tile_direct<D, kDqBK, 256>(smem[0][1], v, it.kv_start, Hkv, hk, T, tid);
 
   bf16x8 qf[NKS], dof[NKS];
   {
@@ -82,51 +118,24 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-  TileStage<D, kDqBK, 256> stK, stV;
   const int n_tiles = (q_end - it.kv_start + kDqBK - 1) / kDqBK;
-  stK.load(k, it.kv_start, Hkv, hk, T, tid);
-  stV.load(v, it.kv_start, Hkv, hk, T, tid);
-  stK.store(smem[0][0], tid);
-  stV.store(smem[0][1], tid);
+  __builtin_amdgcn_s_waitcnt(0);                   // tile 0 has landed in LDS
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kDqBK;
     const char* tK = smem[t & 1][0];
     const char* tV = smem[t & 1][1];
-    stK.load(k, j0 + kDqBK, Hkv, hk, T, tid);      // next tile (clamped rows past the end; unused then)
-    stV.load(v, j0 + kDqBK, Hkv, hk, T, tid);
-    if (j0 <= q0w + 31) {
-      bf16x8 dsf[4];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        floatx16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          s = mfma32(lds_frag_row<D>(tK, 32 * b + l32, 16 * ks + 8 * half), qf[ks], s);
-          dp = mfma32(lds_frag_row<D>(tV, 32 * b + l32, 16 * ks + 8 * half), dof[ks], dp);
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
-          s[r] = (key <= my_row) ? p * (dp[r] - dlt) : 0.f;
-        }
-        dsf[2 * b] = pack8(s, 0);
-        dsf[2 * b + 1] = pack8(s, 8);
-      }
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int ks2 = 0; ks2 < 4; ++ks2)
-          acc[db] = mfma32(lds_frag_tr<D>(tK, 16 * ks2, 32 * db, lane), dsf[ks2], acc[db]);
+    // next tile straight into the other buffer (clamped rows past the end; unused then)
+    stage_tile_direct<D, kDqBK, 256>(smem[(t + 1) & 1][0], k, j0 + kDqBK, Hkv, hk, T, tid);
+    stage_tile_direct<D, kDqBK, 256>(smem[(t + 1) & 1][1], v, j0 + kDqBK, Hkv, hk, T, tid);
+    const int rel = my_row - j0 - 4 * half;
+    if (j0 + kDqBK - 1 <= q0w) {
+      dq_tile<D, false>(tK, tV, qf, dof, acc, c2, lse2, dlt, rel, lane);
+    } else if (j0 <= q0w + 31) {
+      dq_tile<D, true>(tK, tV, qf, dof, acc, c2, lse2, dlt, rel, lane);
     }
-    if (t + 1 < n_tiles) {
-      stK.store(smem[(t + 1) & 1][0], tid);
-      stV.store(smem[(t + 1) & 1][1], tid);
-    }
+    __builtin_amdgcn_s_waitcnt(0);                 // this thread's direct loads have landed
     __syncthreads();
   }
   if (my_row < q_end) {
@@ -144,6 +153,60 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
+// One 32-row query block against this wave's 32 keys.  MASKED blocks touch the diagonal or the end
+// of the query run: rows before the key or at/after q_hi contribute nothing.
+template <int D, bool MASKED>
+__device__ __forceinline__ void dkdv_block(const char* tQ, const char* tDO, const float* s_lse, const float* s_delta,
+                                           int qb, const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
+                                           floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32], float c2, int rel_lo,
+                                           int rel_hi, int lane) {
+  constexpr int NKS = D / 16, NDB = D / 32;
+  constexpr int kPreRow = 4, kPreTr = 4;   // read-ahead depth
+  const int half = lane >> 5, l32 = lane & 31;
+  floatx16 s;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r] = 0.f;
+  // S = Q K^T
+  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_frag_row<D>(tQ, 32 * qb + l32, 16 * i + 8 * half); },
+                              [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
+  // P = exp(S - lse); rows of this C tile: local row 32 qb + 8 (r/4) + 4 half + r%4
+#pragma unroll
+  for (int gq = 0; gq < 4; ++gq) {
+    const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qb + 8 * gq + 4 * half]);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int r = 4 * gq + x, c = 32 * qb + 8 * gq + x;          // c + 4*half = local row
+      const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -l4[x]));
+      s[r] = (MASKED && (c < rel_lo || c >= rel_hi)) ? 0.f : p;
+    }
+  }
+  const bf16x8 pf0 = pack8(s, 0), pf1 = pack8(s, 8);
+  floatx16 dp;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+  // dP = dO V^T
+  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_frag_row<D>(tDO, 32 * qb + l32, 16 * i + 8 * half); },
+                              [&](int i, bf16x8 f) { dp = mfma32(f, vf[i], dp); });
+#pragma unroll
+  for (int gq = 0; gq < 4; ++gq) {
+    const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qb + 8 * gq + 4 * half]);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int r = 4 * gq + x;
+      dp[r] = s[r] * (dp[r] - d4[x]);                                // dS = P (dP - delta)
+    }
+  }
+  const bf16x8 dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
+  // dV^T += dO^T P and dK^T += Q^T dS: transposed dO and Q fragments alternate in one stream
+  frag_pipeline<4 * NDB, kPreTr, 2, 1>(
+      [&](int i) { return lds_frag_tr<D>((i & 1) ? tQ : tDO, 32 * qb + 16 * ((i >> 1) & 1), 32 * (i >> 2), lane); },
+      [&](int i, bf16x8 f) {
+        const int db = i >> 2, ks = (i >> 1) & 1;
+        if (i & 1) dk[db] = mfma32(f, ks ? dsf1 : dsf0, dk[db]);
+        else dv[db] = mfma32(f, ks ? pf1 : pf0, dv[db]);
+      });
+}
+
 template <int D>
 __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                            const bf16* __restrict__ v, const bf16* __restrict__ dO,
@@ -155,7 +218,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
                                                            int load_acc, int store_final) {
   constexpr int NKS = D / 16, NDB = D / 32;
   constexpr int kTileBytes = kQStep * D * 2;
-  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];   // [buffer][Q, dO]
+  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];   // [buffer][Q, dO]
   __shared__ __attribute__((aligned(16))) float s_lse[2][kQStep];
   __shared__ __attribute__((aligned(16))) float s_delta[2][kQStep];
 
@@ -168,6 +231,23 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
   const int kv0w = it.kv_row0 + 32 * wave, my_key = kv0w + l32, kv_end = it.kv_row0 + it.kv_rows;
   const int ld_key = min(my_key, T - 1);
   const float c2 = scale * kLog2e;
+
+  // Flattened walk: for each run, for each head of the group, for each 64-row step.
+  int sgi = it.seg_begin, hh = 0;
+  Seg sg = segs[sgi];
+  int i0 = max(sg.q_lo, it.kv_row0);
+  bool have = true;                                   // a key tile always has at least its own rows
+#define SLIMATTN_STAGE(buf_, row0_, head_)                                                   \
+  do {                                                                                       \
+    stage_tile_direct<D, kQStep, 256>(smem[(buf_)][0], q, (row0_), Hq, (head_), T, tid);     \
+    stage_tile_direct<D, kQStep, 256>(smem[(buf_)][1], dO, (row0_), Hq, (head_), T, tid);    \
+    if (tid < kQStep) {                                                                      \
+      const int r_ = min((row0_) + tid, T - 1);                                              \
+      s_lse[(buf_)][tid] = lse[(size_t)(head_) * T + r_] * kLog2e;                           \
+      s_delta[(buf_)][tid] = delta[(size_t)(head_) * T + r_];                                \
+    }                                                                                        \
+  } while (0)
+  SLIMATTN_STAGE(0, i0, hk * g + hh);
 
   bf16x8 kf[NKS], vf[NKS];
   {
@@ -183,36 +263,13 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
-
-  // Flattened walk: for each run, for each head of the group, for each 64-row step.
-  int sgi = it.seg_begin, hh = 0;
-  Seg sg = segs[sgi];
-  int i0 = max(sg.q_lo, it.kv_row0);
-  bool have = true;                                   // a key tile always has at least its own rows
-  TileStage<D, kQStep, 256> stQ, stDO;
-  float pre_lse = 0.f, pre_delta = 0.f;
-#define SLIMATTN_FETCH(row0_, head_)                                   \
-  do {                                                                 \
-    stQ.load(q, (row0_), Hq, (head_), T, tid);                         \
-    stDO.load(dO, (row0_), Hq, (head_), T, tid);                       \
-    const int r_ = min((row0_) + (tid & (kQStep - 1)), T - 1);         \
-    pre_lse = lse[(size_t)(head_) * T + r_] * kLog2e;                  \
-    pre_delta = delta[(size_t)(head_) * T + r_];                       \
-  } while (0)
-#define SLIMATTN_COMMIT(buf_)                                          \
-  do {                                                                 \
-    stQ.store(smem[(buf_)][0], tid);                                   \
-    stDO.store(smem[(buf_)][1], tid);                                  \
-    if (tid < kQStep) { s_lse[(buf_)][tid] = pre_lse; s_delta[(buf_)][tid] = pre_delta; } \
-  } while (0)
-  SLIMATTN_FETCH(i0, hk * g + hh);
-  SLIMATTN_COMMIT(0);
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   int buf = 0;
   while (have) {
     const int cur_i0 = i0, cur_hi = sg.q_hi;
-    // advance to the next step (uniform across the block)
+    // advance to the next step (uniform across the block) and start fetching it
     i0 += kQStep;
     if (i0 >= sg.q_hi) {
       if (++hh == g) {
@@ -221,53 +278,26 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
       }
       if (have) i0 = max(sg.q_lo, it.kv_row0);
     }
-    SLIMATTN_FETCH(i0, hk * g + hh);                  // after the last step: clamped rows, never committed
+    if (have) SLIMATTN_STAGE(buf ^ 1, i0, hk * g + hh);
 
-    if (cur_i0 + kQStep - 1 >= kv0w) {                // some query row of the step is at or after some key of the wave
-      const char* tQ = smem[buf][0];
-      const char* tDO = smem[buf][1];
-      const bool need_mask = (cur_i0 < kv0w + 31) || (cur_i0 + kQStep > cur_hi);
+    const char* tQ = smem[buf][0];
+    const char* tDO = smem[buf][1];
+    // local rows [rel_lo, rel_hi) minus 4*half contribute: row >= key and row < end of the run
+    const int rel_lo = my_key - cur_i0 - 4 * half, rel_hi = cur_hi - cur_i0 - 4 * half;
 #pragma unroll
-      for (int qb = 0; qb < kQStep / 32; ++qb) {
-        floatx16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          s = mfma32(lds_frag_row<D>(tQ, 32 * qb + l32, 16 * ks + 8 * half), kf[ks], s);
-          dp = mfma32(lds_frag_row<D>(tDO, 32 * qb + l32, 16 * ks + 8 * half), vf[ks], dp);
-        }
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const int rl = 32 * qb + 8 * gq + 4 * half;            // local row of register 4*gq
-          const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[buf][rl]);
-          const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[buf][rl]);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) {
-            const int r = 4 * gq + x;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -l4[x]));
-            if (need_mask) {
-              const int qrow = cur_i0 + rl + x;
-              if (qrow < my_key || qrow >= cur_hi) p = 0.f;
-            }
-            s[r] = p;
-            dp[r] = p * (dp[r] - d4[x]);
-          }
-        }
-        const bf16x8 pf0 = pack8(s, 0), pf1 = pack8(s, 8), dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          dv[db] = mfma32(lds_frag_tr<D>(tDO, 32 * qb, 32 * db, lane), pf0, dv[db]);
-          dv[db] = mfma32(lds_frag_tr<D>(tDO, 32 * qb + 16, 32 * db, lane), pf1, dv[db]);
-          dk[db] = mfma32(lds_frag_tr<D>(tQ, 32 * qb, 32 * db, lane), dsf0, dk[db]);
-          dk[db] = mfma32(lds_frag_tr<D>(tQ, 32 * qb + 16, 32 * db, lane), dsf1, dk[db]);
-        }
-      }
+    for (int qb = 0; qb < kQStep / 32; ++qb) {
+      const int r0 = cur_i0 + 32 * qb;               // first row of the block
+      if (r0 + 31 < kv0w || r0 >= cur_hi) continue;  // wave-uniform: nothing at or after the wave's keys
+      if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)
+        dkdv_block<D, false>(tQ, tDO, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, lane);
+      else
+        dkdv_block<D, true>(tQ, tDO, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, lane);
     }
-    if (have) SLIMATTN_COMMIT(buf ^ 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     buf ^= 1;
   }
+#undef SLIMATTN_STAGE
 
   if (my_key < kv_end) {
     const size_t base = ((size_t)my_key * Hkv + hk) * D;

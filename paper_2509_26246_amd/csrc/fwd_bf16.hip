@@ -5,12 +5,14 @@
 // of 128 rows of one head, walk the sample's keys kv_start .. last row in tiles of 64, keep a
 // running row maximum and row sum, and accumulate O.
 //
-// Shape of the computation on CDNA4: the block's 4 waves own 32 query rows each.  Scores are
+// Shape of the computation on CDNA4: the block's 4 waves own 32 query rows each; two blocks share a
+// compute unit (two waves per SIMD) so one wave's softmax overlaps the other's products.  Scores are
 // produced transposed, S^T = K Q^T (A = K rows from LDS, B = Q held in registers), so that every
 // lane owns one query row: row max / row sum need one cross-lane exchange per tile and the
 // accumulator registers of S^T are, as they stand, the B operand of O^T += V^T P^T.  V^T is read
-// from the row-major V tile with LDS transpose loads.  K and V tiles are double-buffered in LDS;
-// the next tile's global loads are in flight while the current tile is multiplied.
+// from the row-major V tile with LDS transpose loads.  K and V tiles are double-buffered in LDS and
+// filled by direct global->LDS loads issued one tile ahead; operand fragments are read from LDS a
+// few products ahead of their use.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -19,10 +21,70 @@
 namespace slimattn {
 namespace {
 
-constexpr int kFwdBQ = 128;   // query rows per block
+constexpr int kFwdBQ = 128;   // query rows per block: 4 waves x 32 rows
 constexpr int kFwdBK = 64;    // keys per step
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazy = 8.f;  // rescale the accumulators only when a row maximum grew by more than 2^8
+
+// One 64-key tile for this wave's 32 query rows.  MASKED tiles touch the diagonal.
+template <int D, bool MASKED>
+__device__ __forceinline__ void fwd_tile(const char* tK, const char* tV, const bf16x8 (&qf)[D / 16],
+                                         floatx16 (&oacc)[D / 32], float& m_run, float& l_run, float c2, int rel,
+                                         int lane) {
+  constexpr int NKS = D / 16, NDB = D / 32;
+  const int half = lane >> 5, l32 = lane & 31;
+  floatx16 sacc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+  // S^T = K Q^T
+  frag_pipeline<2 * NKS, 4, 1, 1>(
+      [&](int i) { return lds_frag_row<D>(tK, 32 * (i / NKS) + l32, 16 * (i % NKS) + 8 * half); },
+      [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); });
+  if (MASKED) {      // key (j0 + 32b + 8(r/4) + 4 half + r%4) > row  <=>  32b + 8(r/4) + r%4 > rel
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (32 * b + 8 * (r >> 2) + (r & 3) > rel) sacc[b][r] = -INFINITY;
+  }
+  float tmax = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+  for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, fmaxf(sacc[0][r], sacc[1][r]));
+  tmax = fmaxf(tmax, xor32(tmax));
+  // Lazy rescaling: the reference maximum m_run only moves when some row's tile maximum exceeds it
+  // by more than 2^kLazy after scaling; until then probabilities are taken against the old
+  // reference (they may exceed 1 by at most that factor), which leaves O / l unchanged.
+  if (__any((tmax - m_run) * c2 > kLazy)) {
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    m_run = m_new;
+  }
+  const float mc = m_run * c2;
+  float psum = 0.f;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], c2, -mc));
+      sacc[b][r] = p;
+      psum += p;
+    }
+  l_run += psum;
+  bf16x8 pf[4];
+#pragma unroll
+  for (int ks2 = 0; ks2 < 4; ++ks2) pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
+  // O^T += V^T P^T
+  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_frag_tr<D>(tV, 16 * (i & 3), 32 * (i >> 2), lane); },
+                                  [&](int i, bf16x8 f) { oacc[i >> 2] = mfma32(f, pf[i & 3], oacc[i >> 2]); });
+}
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
@@ -32,7 +94,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   constexpr int NKS = D / 16;   // contraction steps over the head dimension
   constexpr int NDB = D / 32;   // 32-wide blocks of the head dimension
   constexpr int kTileBytes = kFwdBK * D * 2;
-  __shared__ __attribute__((aligned(256))) char smem[2][2][kTileBytes];   // [buffer][K, V]
+  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];   // [buffer][K, V]
 
   const int g = Hq / Hkv;
   int item_idx, hk, hg;
@@ -43,6 +105,10 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   const int q0w = it.q_row0 + 32 * wave;          // first query row of this wave
   const int my_row = q0w + l32;                   // the query row this lane owns
   const int q_end = it.q_row0 + it.q_rows;
+
+  const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
+  stage_tile_direct<D, kFwdBK, 256>(smem[0][0], k, it.kv_start, Hkv, hk, T, tid);
+  stage_tile_direct<D, kFwdBK, 256>(smem[0][1], v, it.kv_start, Hkv, hk, T, tid);
 
   bf16x8 qf[NKS];
   {
@@ -55,80 +121,26 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;           // running max (raw q.k units) and this lane's partial row sum
+  float m_run = -INFINITY, l_run = 0.f;           // reference max (raw q.k units) and this lane's partial row sum
   const float c2 = scale * kLog2e;
-
-  TileStage<D, kFwdBK, 256> stK, stV;
-  const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
-  stK.load(k, it.kv_start, Hkv, hk, T, tid);
-  stV.load(v, it.kv_start, Hkv, hk, T, tid);
-  stK.store(smem[0][0], tid);
-  stV.store(smem[0][1], tid);
+  __builtin_amdgcn_s_waitcnt(0);                  // tile 0 has landed in LDS
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kFwdBK;
     const char* tK = smem[t & 1][0];
     const char* tV = smem[t & 1][1];
-    const bool more = t + 1 < n_tiles;
-    stK.load(k, j0 + kFwdBK, Hkv, hk, T, tid);     // past the last tile this reads clamped rows; unused
-    stV.load(v, j0 + kFwdBK, Hkv, hk, T, tid);
-    if (j0 <= q0w + 31) {                          // wave-uniform: some key of the tile is visible to some row
-      floatx16 sacc[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks)
-          sacc[b] = mfma32(lds_frag_row<D>(tK, 32 * b + l32, 16 * ks + 8 * half), qf[ks], sacc[b]);
-      }
-      if (j0 + kFwdBK - 1 > q0w) {                 // tile crosses the diagonal of this wave's rows
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (key > my_row) sacc[b][r] = -INFINITY;
-          }
-      }
-      float tmax = sacc[0][0];
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
-      tmax = fmaxf(tmax, xor32(tmax));
-      const float m_new = fmaxf(m_run, tmax);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-      const float mc = m_new * c2;
-      float psum = 0.f;
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], c2, -mc));
-          sacc[b][r] = p;
-          psum += p;
-        }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-      bf16x8 pf[4];
-#pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int ks2 = 0; ks2 < 4; ++ks2)
-          oacc[db] = mfma32(lds_frag_tr<D>(tV, 16 * ks2, 32 * db, lane), pf[ks2], oacc[db]);
+    // next tile straight into the other buffer (its last readers passed the barrier below);
+    // past the last tile this fetches clamped rows that nobody reads
+    stage_tile_direct<D, kFwdBK, 256>(smem[(t + 1) & 1][0], k, j0 + kFwdBK, Hkv, hk, T, tid);
+    stage_tile_direct<D, kFwdBK, 256>(smem[(t + 1) & 1][1], v, j0 + kFwdBK, Hkv, hk, T, tid);
+    const int rel = my_row - j0 - 4 * half;
+    if (j0 + kFwdBK - 1 <= q0w) {                  // whole tile visible to every row of the wave
+      fwd_tile<D, false>(tK, tV, qf, oacc, m_run, l_run, c2, rel, lane);
+    } else if (j0 <= q0w + 31) {                   // diagonal region
+      fwd_tile<D, true>(tK, tV, qf, oacc, m_run, l_run, c2, rel, lane);
     }
-    if (more) {
-      stK.store(smem[(t + 1) & 1][0], tid);
-      stV.store(smem[(t + 1) & 1][1], tid);
-    }
+    __builtin_amdgcn_s_waitcnt(0);                // this thread's direct loads have landed
     __syncthreads();
   }
 

@@ -65,12 +65,34 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int row0, int co
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// Pack eight fp32 accumulators (registers r0 .. r0+7 of a C tile) into a bf16 B operand.
+// Pack eight fp32 accumulators (registers r0 .. r0+7 of a C tile) into a bf16 B operand
+// (four packed round-to-nearest-even conversions).
+typedef __attribute__((__vector_size__(8 * sizeof(float)))) float floatx8;
 __device__ __forceinline__ bf16x8 pack8(const floatx16& c, int r0) {
-  bf16x8 out;
+  floatx8 t;
 #pragma unroll
-  for (int t = 0; t < 8; ++t) out[t] = (bf16)c[r0 + t];
-  return out;
+  for (int i = 0; i < 8; ++i) t[i] = c[r0 + i];
+  return __builtin_convertvector(t, bf16x8);
+}
+
+// Software-pipelined operand stream: N fragments, each read from LDS kPre steps before the
+// product that consumes it.  `load(i)` returns fragment i, `use(i, frag)` issues its products.
+// The trailing scheduling directives pin the order "kPre reads, then (products, read) ...";
+// rpf = LDS read instructions per fragment, upf = products per fragment.
+template <int N, int kPre, int rpf, int upf, class Load, class Use>
+__device__ __forceinline__ void frag_pipeline(Load&& load, Use&& use) {
+  bf16x8 fr[N];
+#pragma unroll
+  for (int i = 0; i < N + kPre; ++i) {
+    if (i < N) fr[i] = load(i);
+    if (i >= kPre) use(i - kPre, fr[i - kPre]);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, rpf * kPre, 0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, upf, 0);
+    if (i + kPre < N) __builtin_amdgcn_sched_group_barrier(0x100, rpf, 0);
+  }
 }
 
 // Stage ROWS x D bf16 rows [row0, row0+ROWS) of head h of a [T, H, D] tensor: global -> registers.
@@ -96,6 +118,38 @@ struct TileStage {
     }
   }
 };
+
+// Direct global -> LDS staging of a ROWS x D bf16 tile (rows [row0, row0+ROWS) of head h of a
+// [T, H, D] tensor) in the swizzled layout above, without passing through registers: each wave
+// issues 16-byte-per-lane loads whose LDS destination is 1 KiB contiguous (wave-uniform base +
+// lane * 16), so the lane that lands on LDS unit position p of a 256-byte line fetches the global
+// chunk that the swizzle maps to p.  Rows past T-1 are clamped.  Completion: vmcnt, then a barrier.
+template <int D, int ROWS, int NT>
+__device__ __forceinline__ void stage_tile_direct(char* tile, const bf16* __restrict__ base, int row0, int H, int h, int T,
+                                                  int tid) {
+  constexpr int kLines = ROWS * D * 2 / 256;          // 256-byte lines in the tile
+  constexpr int kLinesPerPass = NT / 16;              // 16 lanes per line
+  static_assert(kLines % kLinesPerPass == 0, "tile must divide evenly over the block");
+  const int wave_line0 = (tid >> 6) * 4, lane = tid & 63;
+#pragma unroll
+  for (int i = 0; i < kLines / kLinesPerPass; ++i) {
+    const int line = i * kLinesPerPass + wave_line0 + (lane >> 4), pos = lane & 15;
+    int row, chunk;
+    if (D == 128) {
+      row = line;
+      chunk = pos ^ (((row & 3) << 2) | ((row >> 2) & 3));
+    } else {
+      const int u = pos ^ (((line & 1) << 2) | ((line >> 1) & 3));
+      row = 2 * line + (u >> 3);
+      chunk = u & 7;
+    }
+    const int gr = min(row0 + row, T - 1);
+    const bf16* src = base + ((size_t)gr * H + h) * D + chunk * 8;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(tile + (i * kLinesPerPass + wave_line0) * 256),
+                                     16, 0, 0);
+  }
+}
 
 __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
