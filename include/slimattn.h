@@ -83,7 +83,7 @@ typedef struct slimattn_params {
   int32_t total_tokens;      /* T */
   int32_t n_q_heads;         /* Hq */
   int32_t n_kv_heads;        /* Hkv, divides Hq */
-  int32_t head_dim;          /* d: 64 or 128 (bf16); 16, 32, 64 or 128 (f32) */
+  int32_t head_dim;          /* d: 64 or 128 (bf16; T*Hq*d*2 must stay below 2 GiB); 16, 32, 64 or 128 (f32) */
   int32_t dtype;             /* SLIMATTN_F32 or SLIMATTN_BF16 */
   float   scale;             /* softmax scale applied to q.k */
   int32_t unit_lo, unit_hi;  /* run units [unit_lo, unit_hi) of the pass's list; unit_hi = -1 means all */

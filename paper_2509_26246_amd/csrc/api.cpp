@@ -21,6 +21,8 @@ int check_common(const slimattn_params* p, const slimattn_tables* t, int pass, i
   if (p->dtype == SLIMATTN_BF16 ? !(d == 64 || d == 128) : !(d == 16 || d == 32 || d == 64 || d == 128)) return SLIMATTN_EINVAL;
   if ((int64_t)p->total_tokens != t->total_tokens) return SLIMATTN_EINVAL;
   if (!(p->scale == p->scale)) return SLIMATTN_EINVAL;
+  // the bf16 kernels address tiles with 32-bit byte offsets from a sample's first row
+  if (p->dtype == SLIMATTN_BF16 && (int64_t)p->total_tokens * p->n_q_heads * d * 2 >= (int64_t(1) << 31)) return SLIMATTN_EINVAL;
   *lo = p->unit_lo;
   *hi = p->unit_hi < 0 ? t->n_units[pass] : p->unit_hi;
   if (*lo < 0 || *hi > t->n_units[pass] || *lo > *hi) return SLIMATTN_EINVAL;

@@ -46,12 +46,13 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict_
 
 // ---------------------------------------------------------------------------------------------
 // One 64-key tile of the dQ walk for this wave's 32 query rows.  MASKED tiles touch the diagonal.
+// pk[ks]: this lane's K-fragment address (key block 0, head-dim step ks) in the current buffer; the
+// V tile has the same layout kTileBytes further on.  pkt[db][0..1]: K^T-fragment address pair.
 template <int D, bool MASKED>
-__device__ __forceinline__ void dq_tile(const char* tK, const char* tV, const bf16x8 (&qf)[D / 16],
-                                        const bf16x8 (&dof)[D / 16], floatx16 (&acc)[D / 32], float c2, float lse2,
-                                        float dlt, int rel, int lane) {
-  constexpr int NKS = D / 16, NDB = D / 32;
-  const int half = lane >> 5, l32 = lane & 31;
+__device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pkt)[D / 32][2],
+                                        const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], floatx16 (&acc)[D / 32],
+                                        float c2, float lse2, float dlt, int rel) {
+  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kDqBK * D * 2;
   bf16x8 dsf[4];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
@@ -60,7 +61,7 @@ __device__ __forceinline__ void dq_tile(const char* tK, const char* tV, const bf
     for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dpc[r] = 0.f; }
     // S^T = K Q^T and dP^T = V dO^T for 32 keys: K and V fragments alternate in one stream
     frag_pipeline<2 * NKS, 4, 1, 1>(
-        [&](int i) { return lds_frag_row<D>((i & 1) ? tV : tK, 32 * b + l32, 16 * (i >> 1) + 8 * half); },
+        [&](int i) { return lds_ld_row(pk[i >> 1], b * 32 * kRowBytes + (i & 1) * kTileBytes); },
         [&](int i, bf16x8 f) {
           if (i & 1) dpc = mfma32(f, dof[i >> 1], dpc);
           else sc = mfma32(f, qf[i >> 1], sc);
@@ -75,8 +76,9 @@ __device__ __forceinline__ void dq_tile(const char* tK, const char* tV, const bf
     dsf[2 * b + 1] = pack8(sc, 8);
   }
   // dQ^T += K^T dS^T, K^T fragments by LDS transpose loads
-  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_frag_tr<D>(tK, 16 * (i & 3), 32 * (i >> 2), lane); },
-                                  [&](int i, bf16x8 f) { acc[i >> 2] = mfma32(f, dsf[i & 3], acc[i >> 2]); });
+  frag_pipeline<4 * NDB, 4, 2, 1>(
+      [&](int i) { return lds_ld_tr(pkt[i >> 2][0], pkt[i >> 2][1], (i & 3) * 16 * kRowBytes); },
+      [&](int i, bf16x8 f) { acc[i >> 2] = mfma32(f, dsf[i & 3], acc[i >> 2]); });
 }
 
 template <int D>
@@ -86,8 +88,8 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
                                                          bf16* __restrict__ dQ, const QItem* __restrict__ items, int n_items,
                                                          int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = D / 16, NDB = D / 32;
-  constexpr int kTileBytes = kDqBK * D * 2;
-  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];
+  constexpr int kTileBytes = kDqBK * D * 2, kBufBytes = 2 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes];   // [buffer][K tile, V tile]
 
   const int g = Hq / Hkv;
   int item_idx, hk, hg;
@@ -97,8 +99,11 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int q0w = it.q_row0 + 32 * wave, my_row = q0w + l32, q_end = it.q_row0 + it.q_rows;
   const int ld_row = min(my_row, T - 1);
-  stage_tile_direct<D, kDqBK, 256>(smem[0][0], k, it.kv_start, Hkv, hk, T, tid);
-  stage_tile_direct<D, kDqBK, 256>(smem[0][1], v, it.kv_start, Hkv, hk, T, tid);
+  LDS_PTR(char) lds = (LDS_PTR(char))smem;
+  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  stage_tile<D, kDqBK, 256>(lds, srcK, 0, tid);
+  stage_tile<D, kDqBK, 256>(lds + kTileBytes, srcV, 0, tid);
 
   bf16x8 qf[NKS], dof[NKS];
   {
@@ -112,6 +117,11 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
   const float lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
   const float dlt = delta[(size_t)h * T + ld_row];
   const float c2 = scale * kLog2e;
+  lds_cptr pk[NKS], pkt[NDB][2];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) pk[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) lds_tr_ptrs<D>(lds, 32 * db, lane, pkt[db][0], pkt[db][1]);
   floatx16 acc[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -124,17 +134,21 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kDqBK;
-    const char* tK = smem[t & 1][0];
-    const char* tV = smem[t & 1][1];
-    // next tile straight into the other buffer (clamped rows past the end; unused then)
-    stage_tile_direct<D, kDqBK, 256>(smem[(t + 1) & 1][0], k, j0 + kDqBK, Hkv, hk, T, tid);
-    stage_tile_direct<D, kDqBK, 256>(smem[(t + 1) & 1][1], v, j0 + kDqBK, Hkv, hk, T, tid);
+    // next tile straight into the other buffer (zeros past the end of the tensor; unused then)
+    const int nb = ((t + 1) & 1) * kBufBytes;
+    stage_tile<D, kDqBK, 256>(lds + nb, srcK, (t + 1) * kDqBK, tid);
+    stage_tile<D, kDqBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kDqBK, tid);
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kDqBK - 1 <= q0w) {
-      dq_tile<D, false>(tK, tV, qf, dof, acc, c2, lse2, dlt, rel, lane);
+      dq_tile<D, false>(pk, pkt, qf, dof, acc, c2, lse2, dlt, rel);
     } else if (j0 <= q0w + 31) {
-      dq_tile<D, true>(tK, tV, qf, dof, acc, c2, lse2, dlt, rel, lane);
+      dq_tile<D, true>(pk, pkt, qf, dof, acc, c2, lse2, dlt, rel);
     }
+    const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) pk[ks] += flip;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) { pkt[db][0] += flip; pkt[db][1] += flip; }
     __builtin_amdgcn_s_waitcnt(0);                 // this thread's direct loads have landed
     __syncthreads();
   }
@@ -155,20 +169,22 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 // ---------------------------------------------------------------------------------------------
 // One 32-row query block against this wave's 32 keys.  MASKED blocks touch the diagonal or the end
 // of the query run: rows before the key or at/after q_hi contribute nothing.
+// pq[ks]: this lane's Q-fragment address (query block 0, head-dim step ks) in the current buffer;
+// the dO tile has the same layout kTileBytes further on.  pqt[db][0..1]: Q^T-fragment address pair.
 template <int D, bool MASKED>
-__device__ __forceinline__ void dkdv_block(const char* tQ, const char* tDO, const float* s_lse, const float* s_delta,
-                                           int qb, const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
-                                           floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32], float c2, int rel_lo,
-                                           int rel_hi, int lane) {
-  constexpr int NKS = D / 16, NDB = D / 32;
+__device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const lds_cptr (&pqt)[D / 32][2],
+                                           const float* s_lse, const float* s_delta, int qb, const bf16x8 (&kf)[D / 16],
+                                           const bf16x8 (&vf)[D / 16], floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32],
+                                           float c2, int rel_lo, int rel_hi, int half) {
+  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kQStep * D * 2;
   constexpr int kPreRow = 4, kPreTr = 4;   // read-ahead depth
-  const int half = lane >> 5, l32 = lane & 31;
+  const int qoff = qb * 32 * kRowBytes;
   floatx16 s;
 #pragma unroll
   for (int r = 0; r < 16; ++r) s[r] = 0.f;
   // S = Q K^T
-  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_frag_row<D>(tQ, 32 * qb + l32, 16 * i + 8 * half); },
-                              [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
+  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff); },
+                                    [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
   // P = exp(S - lse); rows of this C tile: local row 32 qb + 8 (r/4) + 4 half + r%4
 #pragma unroll
   for (int gq = 0; gq < 4; ++gq) {
@@ -185,8 +201,8 @@ __device__ __forceinline__ void dkdv_block(const char* tQ, const char* tDO, cons
 #pragma unroll
   for (int r = 0; r < 16; ++r) dp[r] = 0.f;
   // dP = dO V^T
-  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_frag_row<D>(tDO, 32 * qb + l32, 16 * i + 8 * half); },
-                              [&](int i, bf16x8 f) { dp = mfma32(f, vf[i], dp); });
+  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff + kTileBytes); },
+                                    [&](int i, bf16x8 f) { dp = mfma32(f, vf[i], dp); });
 #pragma unroll
   for (int gq = 0; gq < 4; ++gq) {
     const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qb + 8 * gq + 4 * half]);
@@ -199,7 +215,10 @@ __device__ __forceinline__ void dkdv_block(const char* tQ, const char* tDO, cons
   const bf16x8 dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
   // dV^T += dO^T P and dK^T += Q^T dS: transposed dO and Q fragments alternate in one stream
   frag_pipeline<4 * NDB, kPreTr, 2, 1>(
-      [&](int i) { return lds_frag_tr<D>((i & 1) ? tQ : tDO, 32 * qb + 16 * ((i >> 1) & 1), 32 * (i >> 2), lane); },
+      [&](int i) {
+        const int off = qoff + ((i >> 1) & 1) * 16 * kRowBytes + ((i & 1) ? 0 : kTileBytes);
+        return lds_ld_tr(pqt[i >> 2][0], pqt[i >> 2][1], off);
+      },
       [&](int i, bf16x8 f) {
         const int db = i >> 2, ks = (i >> 1) & 1;
         if (i & 1) dk[db] = mfma32(f, ks ? dsf1 : dsf0, dk[db]);
@@ -208,17 +227,14 @@ __device__ __forceinline__ void dkdv_block(const char* tQ, const char* tDO, cons
 }
 
 template <int D>
-__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
-                                                           const bf16* __restrict__ v, const bf16* __restrict__ dO,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           float* __restrict__ acc_dk, float* __restrict__ acc_dv,
-                                                           bf16* __restrict__ dK, bf16* __restrict__ dV,
-                                                           const KvItem* __restrict__ items, int n_items,
-                                                           const Seg* __restrict__ segs, int T, int Hq, int Hkv, float scale,
-                                                           int load_acc, int store_final) {
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(
+    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
+    const float* __restrict__ lse, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
+    bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
+    int T, int Hq, int Hkv, float scale, int load_acc, int store_final) {
   constexpr int NKS = D / 16, NDB = D / 32;
-  constexpr int kTileBytes = kQStep * D * 2;
-  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];   // [buffer][Q, dO]
+  constexpr int kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes];   // [buffer][Q tile, dO tile]
   __shared__ __attribute__((aligned(16))) float s_lse[2][kQStep];
   __shared__ __attribute__((aligned(16))) float s_delta[2][kQStep];
 
@@ -231,21 +247,29 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
   const int kv0w = it.kv_row0 + 32 * wave, my_key = kv0w + l32, kv_end = it.kv_row0 + it.kv_rows;
   const int ld_key = min(my_key, T - 1);
   const float c2 = scale * kLog2e;
+  LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
-  // Flattened walk: for each run, for each head of the group, for each 64-row step.
+  // Flattened walk: for each run, for each head of the group, for each 64-row step.  Rows are
+  // addressed relative to the key tile's first row (every run of the item lies at or after it).
   int sgi = it.seg_begin, hh = 0;
   Seg sg = segs[sgi];
   int i0 = max(sg.q_lo, it.kv_row0);
   bool have = true;                                   // a key tile always has at least its own rows
-#define SLIMATTN_STAGE(buf_, row0_, head_)                                                   \
-  do {                                                                                       \
-    stage_tile_direct<D, kQStep, 256>(smem[(buf_)][0], q, (row0_), Hq, (head_), T, tid);     \
-    stage_tile_direct<D, kQStep, 256>(smem[(buf_)][1], dO, (row0_), Hq, (head_), T, tid);    \
-    if (tid < kQStep) {                                                                      \
-      const int r_ = min((row0_) + tid, T - 1);                                              \
-      s_lse[(buf_)][tid] = lse[(size_t)(head_) * T + r_] * kLog2e;                           \
-      s_delta[(buf_)][tid] = delta[(size_t)(head_) * T + r_];                                \
-    }                                                                                        \
+  const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
+  const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
+  const int head_bytes = D * 2;
+#define SLIMATTN_STAGE(buf_, row0_, head_)                                                                     \
+  do {                                                                                                         \
+    TileSource a_ = srcQ, b_ = srcDO;                                                                          \
+    a_.voff += (head_) * head_bytes;                                                                           \
+    b_.voff += (head_) * head_bytes;                                                                           \
+    stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes, a_, (row0_) - it.kv_row0, tid);                       \
+    stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes + kTileBytes, b_, (row0_) - it.kv_row0, tid);          \
+    if (tid < kQStep) {                                                                                        \
+      const int r_ = min((row0_) + tid, T - 1);                                                                \
+      s_lse[(buf_)][tid] = lse[(size_t)(head_) * T + r_] * kLog2e;                                             \
+      s_delta[(buf_)][tid] = delta[(size_t)(head_) * T + r_];                                                  \
+    }                                                                                                          \
   } while (0)
   SLIMATTN_STAGE(0, i0, hk * g + hh);
 
@@ -258,6 +282,11 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
       vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
     }
   }
+  lds_cptr pq[NKS], pqt[NDB][2];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) pq[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) lds_tr_ptrs<D>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
   floatx16 dk[NDB], dv[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -280,8 +309,6 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
     }
     if (have) SLIMATTN_STAGE(buf ^ 1, i0, hk * g + hh);
 
-    const char* tQ = smem[buf][0];
-    const char* tDO = smem[buf][1];
     // local rows [rel_lo, rel_hi) minus 4*half contribute: row >= key and row < end of the run
     const int rel_lo = my_key - cur_i0 - 4 * half, rel_hi = cur_hi - cur_i0 - 4 * half;
 #pragma unroll
@@ -289,10 +316,15 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(const 
       const int r0 = cur_i0 + 32 * qb;               // first row of the block
       if (r0 + 31 < kv0w || r0 >= cur_hi) continue;  // wave-uniform: nothing at or after the wave's keys
       if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)
-        dkdv_block<D, false>(tQ, tDO, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, lane);
+        dkdv_block<D, false>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, half);
       else
-        dkdv_block<D, true>(tQ, tDO, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, lane);
+        dkdv_block<D, true>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, half);
     }
+    const int flip = buf ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) pq[ks] += flip;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) { pqt[db][0] += flip; pqt[db][1] += flip; }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     buf ^= 1;

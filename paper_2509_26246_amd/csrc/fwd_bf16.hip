@@ -28,21 +28,21 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLazy = 8.f;  // rescale the accumulators only when a row maximum grew by more than 2^8
 
 // One 64-key tile for this wave's 32 query rows.  MASKED tiles touch the diagonal.
+// pk[ks]: this lane's K-fragment address for key block 0 and head-dim step ks; pv[db][0..1]: its
+// V^T-fragment address pair for head-dim block db; both already point into the current buffer.
 template <int D, bool MASKED>
-__device__ __forceinline__ void fwd_tile(const char* tK, const char* tV, const bf16x8 (&qf)[D / 16],
-                                         floatx16 (&oacc)[D / 32], float& m_run, float& l_run, float c2, int rel,
-                                         int lane) {
-  constexpr int NKS = D / 16, NDB = D / 32;
-  const int half = lane >> 5, l32 = lane & 31;
+__device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pv)[D / 32][2],
+                                         const bf16x8 (&qf)[D / 16], floatx16 (&oacc)[D / 32], float& m_run, float& l_run,
+                                         float c2, int rel) {
+  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2;
   floatx16 sacc[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
   // S^T = K Q^T
-  frag_pipeline<2 * NKS, 4, 1, 1>(
-      [&](int i) { return lds_frag_row<D>(tK, 32 * (i / NKS) + l32, 16 * (i % NKS) + 8 * half); },
-      [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); });
+  frag_pipeline<2 * NKS, 4, 1, 1>([&](int i) { return lds_ld_row(pk[i % NKS], (i / NKS) * 32 * kRowBytes); },
+                                  [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); });
   if (MASKED) {      // key (j0 + 32b + 8(r/4) + 4 half + r%4) > row  <=>  32b + 8(r/4) + r%4 > rel
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -50,9 +50,15 @@ __device__ __forceinline__ void fwd_tile(const char* tK, const char* tV, const b
       for (int r = 0; r < 16; ++r)
         if (32 * b + 8 * (r >> 2) + (r & 3) > rel) sacc[b][r] = -INFINITY;
   }
-  float tmax = fmaxf(sacc[0][0], sacc[1][0]);
+  float t4[4];                                    // four independent reduction chains
 #pragma unroll
-  for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, fmaxf(sacc[0][r], sacc[1][r]));
+  for (int c = 0; c < 4; ++c) {
+    t4[c] = max3(sacc[0][4 * c], sacc[0][4 * c + 1], sacc[0][4 * c + 2]);
+    t4[c] = max3(t4[c], sacc[0][4 * c + 3], sacc[1][4 * c]);
+    t4[c] = max3(t4[c], sacc[1][4 * c + 1], sacc[1][4 * c + 2]);
+    t4[c] = fmaxf(t4[c], sacc[1][4 * c + 3]);
+  }
+  float tmax = fmaxf(max3(t4[0], t4[1], t4[2]), t4[3]);
   tmax = fmaxf(tmax, xor32(tmax));
   // Lazy rescaling: the reference maximum m_run only moves when some row's tile maximum exceeds it
   // by more than 2^kLazy after scaling; until then probabilities are taken against the old
@@ -82,7 +88,7 @@ __device__ __forceinline__ void fwd_tile(const char* tK, const char* tV, const b
 #pragma unroll
   for (int ks2 = 0; ks2 < 4; ++ks2) pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
   // O^T += V^T P^T
-  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_frag_tr<D>(tV, 16 * (i & 3), 32 * (i >> 2), lane); },
+  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_ld_tr(pv[i >> 2][0], pv[i >> 2][1], (i & 3) * 16 * kRowBytes); },
                                   [&](int i, bf16x8 f) { oacc[i >> 2] = mfma32(f, pf[i & 3], oacc[i >> 2]); });
 }
 
@@ -93,8 +99,8 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
                                                           int n_items, int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = D / 16;   // contraction steps over the head dimension
   constexpr int NDB = D / 32;   // 32-wide blocks of the head dimension
-  constexpr int kTileBytes = kFwdBK * D * 2;
-  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];   // [buffer][K, V]
+  constexpr int kTileBytes = kFwdBK * D * 2, kBufBytes = 2 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes];   // [buffer][K tile, V tile]
 
   const int g = Hq / Hkv;
   int item_idx, hk, hg;
@@ -105,10 +111,13 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   const int q0w = it.q_row0 + 32 * wave;          // first query row of this wave
   const int my_row = q0w + l32;                   // the query row this lane owns
   const int q_end = it.q_row0 + it.q_rows;
+  LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
   const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
-  stage_tile_direct<D, kFwdBK, 256>(smem[0][0], k, it.kv_start, Hkv, hk, T, tid);
-  stage_tile_direct<D, kFwdBK, 256>(smem[0][1], v, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  stage_tile<D, kFwdBK, 256>(lds, srcK, 0, tid);
+  stage_tile<D, kFwdBK, 256>(lds + kTileBytes, srcV, 0, tid);
 
   bf16x8 qf[NKS];
   {
@@ -116,6 +125,11 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
+  lds_cptr pk[NKS], pv[NDB][2];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) pk[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) lds_tr_ptrs<D>(lds + kTileBytes, 32 * db, lane, pv[db][0], pv[db][1]);
   floatx16 oacc[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -128,18 +142,22 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kFwdBK;
-    const char* tK = smem[t & 1][0];
-    const char* tV = smem[t & 1][1];
     // next tile straight into the other buffer (its last readers passed the barrier below);
-    // past the last tile this fetches clamped rows that nobody reads
-    stage_tile_direct<D, kFwdBK, 256>(smem[(t + 1) & 1][0], k, j0 + kFwdBK, Hkv, hk, T, tid);
-    stage_tile_direct<D, kFwdBK, 256>(smem[(t + 1) & 1][1], v, j0 + kFwdBK, Hkv, hk, T, tid);
+    // past the end of the tensor the loads return zeros that nobody uses
+    const int nb = ((t + 1) & 1) * kBufBytes;
+    stage_tile<D, kFwdBK, 256>(lds + nb, srcK, (t + 1) * kFwdBK, tid);
+    stage_tile<D, kFwdBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kFwdBK, tid);
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kFwdBK - 1 <= q0w) {                  // whole tile visible to every row of the wave
-      fwd_tile<D, false>(tK, tV, qf, oacc, m_run, l_run, c2, rel, lane);
+      fwd_tile<D, false>(pk, pv, qf, oacc, m_run, l_run, c2, rel);
     } else if (j0 <= q0w + 31) {                   // diagonal region
-      fwd_tile<D, true>(tK, tV, qf, oacc, m_run, l_run, c2, rel, lane);
+      fwd_tile<D, true>(pk, pv, qf, oacc, m_run, l_run, c2, rel);
     }
+    const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) pk[ks] += flip;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) { pv[db][0] += flip; pv[db][1] += flip; }
     __builtin_amdgcn_s_waitcnt(0);                // this thread's direct loads have landed
     __syncthreads();
   }

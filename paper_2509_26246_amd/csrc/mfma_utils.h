@@ -151,6 +151,94 @@ __device__ __forceinline__ void stage_tile_direct(char* tile, const bf16* __rest
   }
 }
 
+// ---- LDS fragment pointers kept in registers --------------------------------------------------
+// The swizzle makes a fragment's LDS address a non-additive function of (lane, column block), so
+// the per-lane addresses are computed once, kept in registers (laundered through an empty asm so
+// the compiler does not recompute them at every use) and advanced by adding uniform byte offsets:
+// rows are additive, and so is the buffer switch.
+typedef LDS_PTR(const char) lds_cptr;
+
+__device__ __forceinline__ lds_cptr keep(lds_cptr p) {
+  asm volatile("" : "+v"(p));
+  return p;
+}
+template <int D>
+__device__ __forceinline__ lds_cptr lds_row_ptr(lds_cptr tile, int row, int col0) {
+  return keep(tile + lds_off16<D>(row, col0 >> 3));
+}
+// Pointers for lds_frag_tr at row0 = 0: p0 serves rows {4*half + 0..3}, p1 rows {8 + 4*half + 0..3};
+// a fragment at row0 = 16*s is read at both pointers + 16*s*(2*D) bytes.
+template <int D>
+__device__ __forceinline__ void lds_tr_ptrs(lds_cptr tile, int col0, int lane, lds_cptr& p0, lds_cptr& p1) {
+  const int i = lane & 15, grp = lane >> 4;
+  const int row = 4 * (grp >> 1) + (i >> 2);
+  const int col = col0 + 16 * (grp & 1) + 4 * (i & 3);
+  p0 = keep(tile + lds_off16<D>(row, col >> 3) + ((col & 4) << 1));
+  p1 = keep(tile + lds_off16<D>(row + 8, col >> 3) + ((col & 4) << 1));
+}
+__device__ __forceinline__ bf16x8 lds_ld_row(lds_cptr p, int byte_off) {
+  return *reinterpret_cast<LDS_PTR(const bf16x8)>(p + byte_off);
+}
+__device__ __forceinline__ bf16x8 lds_ld_tr(lds_cptr p0, lds_cptr p1, int byte_off) {
+  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(p0 + byte_off));
+  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(p1 + byte_off));
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+  short8v r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// ---- global -> LDS staging through buffer loads -----------------------------------------------
+// A TileSource addresses the rows of one head of a [T, H, D] bf16 tensor starting at row `row_base`
+// through a raw buffer descriptor whose range ends with the tensor: rows past the end read as
+// zeros (they are never used unmasked), so no clamping is needed, and a tile's address is a
+// per-lane constant (voff) plus a wave-uniform scalar.  The bytes from row_base to the end of
+// what a kernel touches must stay below 4 GiB (checked on the host).
+struct TileSource {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int voff;        // this lane's byte offset within one pass of 256-byte lines
+  int row_bytes;   // H * D * 2
+};
+template <int D, int NT>
+__device__ __forceinline__ TileSource make_tile_source(const bf16* base, int row_base, int H, int h, int T, int tid) {
+  TileSource s;
+  const size_t first = ((size_t)row_base * H + h) * D;
+  const size_t valid = ((size_t)T * H * D - first) * 2;
+  s.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(base + first), 0, (int)(valid > 0xFFFFFFFFull ? 0xFFFFFFFFull : valid),
+                                             0x00020000);
+  s.row_bytes = H * D * 2;
+  const int wave = tid >> 6, lane = tid & 63, pos = lane & 15;
+  const int line = wave * 4 + (lane >> 4);            // line within a pass; the swizzle repeats every pass
+  int row, chunk;
+  if (D == 128) {
+    row = line;
+    chunk = pos ^ (((row & 3) << 2) | ((row >> 2) & 3));
+  } else {
+    const int u = pos ^ (((line & 1) << 2) | ((line >> 1) & 3));
+    row = 2 * line + (u >> 3);
+    chunk = u & 7;
+  }
+  s.voff = row * s.row_bytes + chunk * 16;
+  return s;
+}
+// Issues the loads for rows [row_base + row0, +ROWS) into `tile` (swizzled layout).  Completion is
+// tracked by vmcnt; a barrier must follow before other waves read the tile.
+template <int D, int ROWS, int NT>
+__device__ __forceinline__ void stage_tile(LDS_PTR(char) tile, const TileSource& s, int row0, int tid) {
+  constexpr int kLines = ROWS * D * 2 / 256, kLinesPerPass = NT / 16, kRowsPerPass = kLinesPerPass * 256 / (D * 2);
+  static_assert(kLines % kLinesPerPass == 0, "tile must divide evenly over the block");
+  const int wave_line0 = (tid >> 6) * 4;
+#pragma unroll
+  for (int i = 0; i < kLines / kLinesPerPass; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, tile + (i * kLinesPerPass + wave_line0) * 256, 16, s.voff,
+                                             (row0 + i * kRowsPerPass) * s.row_bytes, 0, 0);
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
