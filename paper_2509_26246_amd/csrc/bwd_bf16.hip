@@ -51,15 +51,16 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict_
 template <int D, bool MASKED>
 __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pkt)[D / 32][2],
                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], floatx16 (&acc)[D / 32],
-                                        float c2, float lse2, float dlt, int rel) {
+                                        float lse2, float dlt, int rel) {
   constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kDqBK * D * 2;
   bf16x8 dsf[4];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     floatx16 sc, dpc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dpc[r] = 0.f; }
-    // S^T = K Q^T and dP^T = V dO^T for 32 keys: K and V fragments alternate in one stream
+    for (int r = 0; r < 16; ++r) { sc[r] = -lse2; dpc[r] = 0.f; }
+    // S^T = K Q^T - lse (log2 units: qf holds q * scale * log2 e) and dP^T = V dO^T for 32 keys:
+    // K and V fragments alternate in one stream
     frag_pipeline<2 * NKS, 4, 1, 1>(
         [&](int i) { return lds_ld_row(pk[i >> 1], b * 32 * kRowBytes + (i & 1) * kTileBytes); },
         [&](int i, bf16x8 f) {
@@ -68,7 +69,7 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
         });
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], c2, -lse2));
+      const float p = __builtin_amdgcn_exp2f(sc[r]);
       const float ds = p * (dpc[r] - dlt);
       sc[r] = (MASKED && 32 * b + 8 * (r >> 2) + (r & 3) > rel) ? 0.f : ds;   // key > row contributes nothing
     }
@@ -110,13 +111,12 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
     const size_t off = ((size_t)ld_row * Hq + h) * D + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + 16 * ks);
+      qf[ks] = scale8(*reinterpret_cast<const bf16x8*>(q + off + 16 * ks), scale * kLog2e);
       dof[ks] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * ks);
     }
   }
   const float lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
   const float dlt = delta[(size_t)h * T + ld_row];
-  const float c2 = scale * kLog2e;
   lds_cptr pk[NKS], pkt[NDB][2];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) pk[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
@@ -140,9 +140,9 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
     stage_tile<D, kDqBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kDqBK, tid);
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kDqBK - 1 <= q0w) {
-      dq_tile<D, false>(pk, pkt, qf, dof, acc, c2, lse2, dlt, rel);
+      dq_tile<D, false>(pk, pkt, qf, dof, acc, lse2, dlt, rel);
     } else if (j0 <= q0w + 31) {
-      dq_tile<D, true>(pk, pkt, qf, dof, acc, c2, lse2, dlt, rel);
+      dq_tile<D, true>(pk, pkt, qf, dof, acc, lse2, dlt, rel);
     }
     const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
 #pragma unroll
@@ -175,26 +175,27 @@ template <int D, bool MASKED>
 __device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const lds_cptr (&pqt)[D / 32][2],
                                            const float* s_lse, const float* s_delta, int qb, const bf16x8 (&kf)[D / 16],
                                            const bf16x8 (&vf)[D / 16], floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32],
-                                           float c2, int rel_lo, int rel_hi, int half) {
+                                           int rel_lo, int rel_hi, int half) {
   constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kQStep * D * 2;
-  constexpr int kPreRow = 4, kPreTr = 4;   // read-ahead depth
+  constexpr int kPreRow = D == 128 ? 2 : 4, kPreTr = D == 128 ? 2 : 4;   // read-ahead depth, bounded by registers
   const int qoff = qb * 32 * kRowBytes;
+  // S = Q K^T - lse in log2 units (kf holds k * scale * log2 e); the accumulator starts at -lse of
+  // its row: local row 32 qb + 8 (r/4) + 4 half + r%4
   floatx16 s;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s[r] = 0.f;
-  // S = Q K^T
-  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff); },
-                                    [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
-  // P = exp(S - lse); rows of this C tile: local row 32 qb + 8 (r/4) + 4 half + r%4
 #pragma unroll
   for (int gq = 0; gq < 4; ++gq) {
     const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qb + 8 * gq + 4 * half]);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int r = 4 * gq + x, c = 32 * qb + 8 * gq + x;          // c + 4*half = local row
-      const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -l4[x]));
-      s[r] = (MASKED && (c < rel_lo || c >= rel_hi)) ? 0.f : p;
-    }
+    for (int x = 0; x < 4; ++x) s[4 * gq + x] = -l4[x];
+  }
+  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff); },
+                                    [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
+  // P = exp(S - lse)
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int c = 32 * qb + 8 * (r >> 2) + (r & 3);                 // c + 4*half = local row
+    const float p = __builtin_amdgcn_exp2f(s[r]);
+    s[r] = (MASKED && (c < rel_lo || c >= rel_hi)) ? 0.f : p;
   }
   const bf16x8 pf0 = pack8(s, 0), pf1 = pack8(s, 8);
   floatx16 dp;
@@ -227,7 +228,7 @@ __device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const l
 }
 
 template <int D>
-__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(
+__global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const float* __restrict__ lse, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
@@ -246,7 +247,6 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int kv0w = it.kv_row0 + 32 * wave, my_key = kv0w + l32, kv_end = it.kv_row0 + it.kv_rows;
   const int ld_key = min(my_key, T - 1);
-  const float c2 = scale * kLog2e;
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
   // Flattened walk: for each run, for each head of the group, for each 64-row step.  Rows are
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(
     const size_t off = ((size_t)ld_key * Hkv + hk) * D + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + 16 * ks);
+      kf[ks] = scale8(*reinterpret_cast<const bf16x8*>(k + off + 16 * ks), scale * kLog2e);
       vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
     }
   }
@@ -316,9 +316,9 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void dkdv_bf16_kernel(
       const int r0 = cur_i0 + 32 * qb;               // first row of the block
       if (r0 + 31 < kv0w || r0 >= cur_hi) continue;  // wave-uniform: nothing at or after the wave's keys
       if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)
-        dkdv_block<D, false>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, half);
+        dkdv_block<D, false>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, rel_lo, rel_hi, half);
       else
-        dkdv_block<D, true>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, c2, rel_lo, rel_hi, half);
+        dkdv_block<D, true>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, rel_lo, rel_hi, half);
     }
     const int flip = buf ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
 #pragma unroll

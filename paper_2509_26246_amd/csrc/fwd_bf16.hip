@@ -30,17 +30,21 @@ constexpr float kLazy = 8.f;  // rescale the accumulators only when a row maximu
 // One 64-key tile for this wave's 32 query rows.  MASKED tiles touch the diagonal.
 // pk[ks]: this lane's K-fragment address for key block 0 and head-dim step ks; pv[db][0..1]: its
 // V^T-fragment address pair for head-dim block db; both already point into the current buffer.
+// qf holds q * scale * log2(e), so the products are scores in log2 units; the accumulators start
+// at minus the row's reference maximum m_ref, so they come out as the exponents directly.
+__device__ __forceinline__ int fbits(float x) { return __builtin_bit_cast(int, x); }
+
 template <int D, bool MASKED>
 __device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pv)[D / 32][2],
-                                         const bf16x8 (&qf)[D / 16], floatx16 (&oacc)[D / 32], float& m_run, float& l_run,
-                                         float c2, int rel) {
+                                         const bf16x8 (&qf)[D / 16], floatx16 (&oacc)[D / 32], float& m_ref, float& l_run,
+                                         int rel) {
   constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2;
   floatx16 sacc[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
-  // S^T = K Q^T
+    for (int r = 0; r < 16; ++r) sacc[b][r] = -m_ref;
+  // S^T = K Q^T (minus the reference maximum)
   frag_pipeline<2 * NKS, 4, 1, 1>([&](int i) { return lds_ld_row(pk[i % NKS], (i / NKS) * 32 * kRowBytes); },
                                   [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); });
   if (MASKED) {      // key (j0 + 32b + 8(r/4) + 4 half + r%4) > row  <=>  32b + 8(r/4) + r%4 > rel
@@ -50,43 +54,51 @@ __device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds
       for (int r = 0; r < 16; ++r)
         if (32 * b + 8 * (r >> 2) + (r & 3) > rel) sacc[b][r] = -INFINITY;
   }
-  float t4[4];                                    // four independent reduction chains
+  {
+    // Lazy rescaling: the reference only moves when some row's tile maximum exceeds it by more than
+    // 2^kLazy (wave-uniform test).  Probabilities may therefore exceed 1 by at most that factor;
+    // O / l is unaffected.  The reference starts at the row's score against the sample's first key
+    // (always visible), so m_ref <= true running maximum (+ rounding) <= m_ref + kLazy throughout
+    // and row sums cannot underflow.  Only a positive excess matters, and positive floats
+    // order like their bit patterns, so the maximum is taken on the bit patterns as integers
+    // (a row whose scores are all below the reference yields some negative value: no rescale).
+    int t4[4];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    t4[c] = max3(sacc[0][4 * c], sacc[0][4 * c + 1], sacc[0][4 * c + 2]);
-    t4[c] = max3(t4[c], sacc[0][4 * c + 3], sacc[1][4 * c]);
-    t4[c] = max3(t4[c], sacc[1][4 * c + 1], sacc[1][4 * c + 2]);
-    t4[c] = fmaxf(t4[c], sacc[1][4 * c + 3]);
+    for (int c = 0; c < 4; ++c) {
+      t4[c] = max(max(fbits(sacc[0][4 * c]), fbits(sacc[0][4 * c + 1])), fbits(sacc[0][4 * c + 2]));
+      t4[c] = max(max(t4[c], fbits(sacc[0][4 * c + 3])), fbits(sacc[1][4 * c]));
+      t4[c] = max(max(t4[c], fbits(sacc[1][4 * c + 1])), fbits(sacc[1][4 * c + 2]));
+      t4[c] = max(t4[c], fbits(sacc[1][4 * c + 3]));
+    }
+    int imax = max(max(max(t4[0], t4[1]), t4[2]), t4[3]);
+    imax = max(imax, __shfl_xor(imax, 32));
+    if (__any(imax > fbits(kLazy))) {
+      const float shift = imax > 0 ? __builtin_bit_cast(float, imax) : 0.f;
+      const float alpha = __builtin_amdgcn_exp2f(-shift);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[b][r] -= shift;
+      m_ref += shift;
+    }
   }
-  float tmax = fmaxf(max3(t4[0], t4[1], t4[2]), t4[3]);
-  tmax = fmaxf(tmax, xor32(tmax));
-  // Lazy rescaling: the reference maximum m_run only moves when some row's tile maximum exceeds it
-  // by more than 2^kLazy after scaling; until then probabilities are taken against the old
-  // reference (they may exceed 1 by at most that factor), which leaves O / l unchanged.
-  if (__any((tmax - m_run) * c2 > kLazy)) {
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    l_run *= alpha;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    m_run = m_new;
-  }
-  const float mc = m_run * c2;
-  float psum = 0.f;
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], c2, -mc));
-      sacc[b][r] = p;
-      psum += p;
-    }
-  l_run += psum;
+    for (int r = 0; r < 16; ++r) sacc[b][r] = __builtin_amdgcn_exp2f(sacc[b][r]);
   bf16x8 pf[4];
+  float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int ks2 = 0; ks2 < 4; ++ks2) pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
+  for (int ks2 = 0; ks2 < 4; ++ks2) {
+    pf[ks2] = pack8(sacc[ks2 >> 1], 8 * (ks2 & 1));
+    ps[ks2] = sum8(pf[ks2], ps[ks2]);             // row sum of the rounded probabilities the product uses
+  }
+  l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
   // O^T += V^T P^T
   frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_ld_tr(pv[i >> 2][0], pv[i >> 2][1], (i & 3) * 16 * kRowBytes); },
                                   [&](int i, bf16x8 f) { oacc[i >> 2] = mfma32(f, pf[i & 3], oacc[i >> 2]); });
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   {
     const bf16* qp = q + ((size_t)min(my_row, T - 1) * Hq + h) * D + 8 * half;
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = scale8(*reinterpret_cast<const bf16x8*>(qp + 16 * ks), scale * kLog2e);
   }
   lds_cptr pk[NKS], pv[NDB][2];
 #pragma unroll
@@ -135,8 +147,18 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;           // reference max (raw q.k units) and this lane's partial row sum
-  const float c2 = scale * kLog2e;
+  // reference maximum (log2 units): the row's score against the first key of the sample
+  float m_ref = 0.f, l_run = 0.f;
+  {
+    const bf16* kp = k + ((size_t)it.kv_start * Hkv + hk) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) m_ref = fmaf((float)qf[ks][e], (float)k0[e], m_ref);
+    }
+    m_ref += xor32(m_ref);
+  }
   __builtin_amdgcn_s_waitcnt(0);                  // tile 0 has landed in LDS
   __syncthreads();
 
@@ -149,9 +171,9 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     stage_tile<D, kFwdBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kFwdBK, tid);
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kFwdBK - 1 <= q0w) {                  // whole tile visible to every row of the wave
-      fwd_tile<D, false>(pk, pv, qf, oacc, m_run, l_run, c2, rel);
+      fwd_tile<D, false>(pk, pv, qf, oacc, m_ref, l_run, rel);
     } else if (j0 <= q0w + 31) {                   // diagonal region
-      fwd_tile<D, true>(pk, pv, qf, oacc, m_run, l_run, c2, rel);
+      fwd_tile<D, true>(pk, pv, qf, oacc, m_ref, l_run, rel);
     }
     const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
 #pragma unroll
@@ -175,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
         for (int x = 0; x < 4; ++x) w[x] = (bf16)(oacc[db][4 * gq + x] * inv);
         *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq + 4 * half) = w;
       }
-    if (half == 0) lse[(size_t)h * T + my_row] = m_run * scale + __builtin_amdgcn_logf(l_tot) * kLn2;
+    if (half == 0) lse[(size_t)h * T + my_row] = (m_ref + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
 }
 

@@ -75,6 +75,27 @@ __device__ __forceinline__ bf16x8 pack8(const floatx16& c, int r0) {
   return __builtin_convertvector(t, bf16x8);
 }
 
+// Fragment of eight bf16 values times a scalar, rounded back to bf16 (used to fold the softmax
+// scale, in log2 units, into one operand of the score product).
+__device__ __forceinline__ bf16x8 scale8(bf16x8 a, float c) {
+  floatx8 t = __builtin_convertvector(a, floatx8);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t[i] *= c;
+  return __builtin_convertvector(t, bf16x8);
+}
+
+// Sum of the eight bf16 values of a fragment, added to acc (four dot-products against ones).
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+__device__ __forceinline__ float sum8(bf16x8 a, float acc) {
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bf16x2 pr = {a[2 * i], a[2 * i + 1]};
+    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+  }
+  return acc;
+}
+
 // Software-pipelined operand stream: N fragments, each read from LDS kPre steps before the
 // product that consumes it.  `load(i)` returns fragment i, `use(i, frag)` issues its products.
 // The trailing scheduling directives pin the order "kPre reads, then (products, read) ...";
@@ -231,12 +252,6 @@ __device__ __forceinline__ void stage_tile(LDS_PTR(char) tile, const TileSource&
   for (int i = 0; i < kLines / kLinesPerPass; ++i)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, tile + (i * kLinesPerPass + wave_line0) * 256, 16, s.voff,
                                              (row0 + i * kRowsPerPass) * s.row_bytes, 0, 0);
-}
-
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float d;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
 }
 
 __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
