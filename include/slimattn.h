@@ -151,7 +151,7 @@ void slimattn_tables_destroy(slimattn_tables* t);
 /* Counts held by a handle: what = 0 tokens, 1 samples, 2 slices, 3 forward units, 4 backward units. */
 int64_t slimattn_tables_count(const slimattn_tables* t, int what);
 
-/* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators + row statistic). */
+/* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators + two per-row statistics). */
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t n_q_heads, int32_t n_kv_heads,
                                     int32_t head_dim);
 

@@ -110,6 +110,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   float* acc_dk = (float*)workspace;
   float* acc_dv = acc_dk + acc_elems;
   float* delta = (float*)((char*)workspace + align_up(2 * acc_elems * sizeof(float)));
+  float* lse2 = (float*)((char*)delta + align_up(T * p->n_q_heads * sizeof(float)));   // bf16 path: lse in log2 units
   const LaunchCtx ctx{p, stream, t->total_tokens};
   const int n_units = t->n_units[1];
   const bool whole = lo == 0 && hi == n_units;
@@ -118,7 +119,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
     rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
       return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
-                 : launch_bwd_delta_bf16(ctx, o, dO, delta);
+                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2);
     }));
     if (rc != SLIMATTN_OK) return rc;
   }
@@ -128,7 +129,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     return timed(SLIMATTN_K_DQ, stream, [&] {
       return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
                                      (float*)dQ, items, n)
-                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse, delta, dQ, items, n);
+                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse2, delta, dQ, items, n);
     });
   };
   auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {
@@ -136,7 +137,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
       return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
                                        delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
                                        store_final)
-                 : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                 : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
                                         store_final);
     });
   };

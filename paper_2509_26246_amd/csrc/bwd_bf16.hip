@@ -21,13 +21,17 @@ namespace slimattn {
 namespace {
 
 constexpr int kDqBQ = 128, kDqBK = 64;
-constexpr int kKvOwn = 128, kQStep = 64;
+constexpr int kKvOwn = 128;
+// query rows per step of the dK/dV walk: at head_dim 128 the wave's V fragments live in LDS and the
+// step is 32 rows, which keeps the kernel at two waves per SIMD without register spills
+template <int D> struct DkdvCfg { static constexpr int kQStep = D == 128 ? 32 : 64; static constexpr bool kVInLds = D == 128; };
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dO,
-                                                         float* __restrict__ delta, int T, int Hq) {
+                                                         const float* __restrict__ lse, float* __restrict__ delta,
+                                                         float* __restrict__ lse2, int T, int Hq) {
   constexpr int LPR = D / 8;                                   // lanes per (row, head)
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t rh = idx / LPR;                                // row * Hq + head
@@ -41,7 +45,11 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict_
   }
 #pragma unroll
   for (int w = LPR / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w);
-  if (live && (idx % LPR) == 0) delta[(size_t)(rh % Hq) * T + (rh / Hq)] = s;
+  if (live && (idx % LPR) == 0) {
+    const size_t at = (size_t)(rh % Hq) * T + (rh / Hq);
+    delta[at] = s;
+    lse2[at] = lse[at] * kLog2e;                                // the row statistic in log2 units, for exp2
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -76,16 +84,23 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
     dsf[2 * b] = pack8(sc, 0);
     dsf[2 * b + 1] = pack8(sc, 8);
   }
-  // dQ^T += K^T dS^T, K^T fragments by LDS transpose loads
-  frag_pipeline<4 * NDB, 4, 2, 1>(
-      [&](int i) { return lds_ld_tr(pkt[i >> 2][0], pkt[i >> 2][1], (i & 3) * 16 * kRowBytes); },
-      [&](int i, bf16x8 f) { acc[i >> 2] = mfma32(f, dsf[i & 3], acc[i >> 2]); });
+  // dQ^T += K^T dS^T: one batch of four K^T fragments (the four 16-key steps) per head-dim block
+  Tr4 tb[NDB];
+  constexpr int kStep = 16 * kRowBytes;
+  tr4_issue<0, kStep, 2 * kStep, 3 * kStep>(pkt[0][0], pkt[0][1], tb[0]);
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    if (db + 1 < NDB) tr4_issue_wait<0, kStep, 2 * kStep, 3 * kStep>(pkt[db + 1][0], pkt[db + 1][1], tb[db + 1], tb[db]);
+    else tr4_wait(tb[db]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[db] = mfma32(tr4_frag(tb[db], j), dsf[j], acc[db]);
+  }
 }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                          const bf16* __restrict__ v, const bf16* __restrict__ dO,
-                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         const float* __restrict__ lse2_all, const float* __restrict__ delta,
                                                          bf16* __restrict__ dQ, const QItem* __restrict__ items, int n_items,
                                                          int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = D / 16, NDB = D / 32;
@@ -115,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
       dof[ks] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * ks);
     }
   }
-  const float lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
+  const float lse2 = lse2_all[(size_t)h * T + ld_row];
   const float dlt = delta[(size_t)h * T + ld_row];
   lds_cptr pk[NKS], pkt[NDB][2];
 #pragma unroll
@@ -167,18 +182,21 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// One 32-row query block against this wave's 32 keys.  MASKED blocks touch the diagonal or the end
-// of the query run: rows before the key or at/after q_hi contribute nothing.
-// pq[ks]: this lane's Q-fragment address (query block 0, head-dim step ks) in the current buffer;
-// the dO tile has the same layout kTileBytes further on.  pqt[db][0..1]: Q^T-fragment address pair.
-template <int D, bool MASKED>
-__device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const lds_cptr (&pqt)[D / 32][2],
-                                           const float* s_lse, const float* s_delta, int qb, const bf16x8 (&kf)[D / 16],
+// One 32-row query block (QB) of the step staged in LDS buffer BUF against this wave's 32 keys.
+// MASKED blocks touch the diagonal or the end of the query run: rows before the key or at/after
+// q_hi contribute nothing.
+// pq[ks]: this lane's Q-fragment address (buffer 0, query block 0, head-dim step ks); the dO tile
+// has the same layout kTileBytes further on, buffer 1 kBufBytes further on.  pqt[db][0..1]:
+// Q^T-fragment address pair.  v_rel: byte distance from pq[] to this wave's V fragments (when the
+// V tile lives in LDS).
+template <int D, bool MASKED, int QB, int BUF>
+__device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const lds_cptr (&pqt)[D / 32][2], int v_rel,
+                                           const float* s_lse, const float* s_delta, const bf16x8 (&kf)[D / 16],
                                            const bf16x8 (&vf)[D / 16], floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32],
                                            int rel_lo, int rel_hi, int half) {
-  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kQStep * D * 2;
-  constexpr int kPreRow = D == 128 ? 2 : 4, kPreTr = D == 128 ? 2 : 4;   // read-ahead depth, bounded by registers
-  const int qoff = qb * 32 * kRowBytes;
+  constexpr int kQStep = DkdvCfg<D>::kQStep;
+  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes;
+  constexpr int qb = QB, qoff = BUF * kBufBytes + QB * 32 * kRowBytes;
   // S = Q K^T - lse in log2 units (kf holds k * scale * log2 e); the accumulator starts at -lse of
   // its row: local row 32 qb + 8 (r/4) + 4 half + r%4
   floatx16 s;
@@ -188,8 +206,17 @@ __device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const l
 #pragma unroll
     for (int x = 0; x < 4; ++x) s[4 * gq + x] = -l4[x];
   }
-  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff); },
-                                    [&](int i, bf16x8 f) { s = mfma32(f, kf[i], s); });
+  {   // batches of two Q fragments
+    R2 rb[NKS / 2];
+    r2_issue<qoff, qoff>(pq[0], pq[1], rb[0]);
+#pragma unroll
+    for (int j = 0; j < NKS / 2; ++j) {
+      if (j + 1 < NKS / 2) r2_issue_wait<qoff, qoff>(pq[2 * j + 2], pq[2 * j + 3], rb[j + 1], rb[j]);
+      else r2_wait(rb[j]);
+      s = mfma32(rb[j].f[0], kf[2 * j], s);
+      s = mfma32(rb[j].f[1], kf[2 * j + 1], s);
+    }
+  }
   // P = exp(S - lse)
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -202,8 +229,27 @@ __device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const l
 #pragma unroll
   for (int r = 0; r < 16; ++r) dp[r] = 0.f;
   // dP = dO V^T
-  frag_pipeline<NKS, kPreRow, 1, 1>([&](int i) { return lds_ld_row(pq[i], qoff + kTileBytes); },
-                                    [&](int i, bf16x8 f) { dp = mfma32(f, vf[i], dp); });
+  constexpr int doff = qoff + kTileBytes;
+  if (DkdvCfg<D>::kVInLds) {   // both operands come from LDS: one (dO fragment, V fragment) pair per batch
+    R2 rb[NKS];
+    r2_issue<doff, 0>(pq[0], pq[0] + v_rel, rb[0]);
+#pragma unroll
+    for (int j = 0; j < NKS; ++j) {
+      if (j + 1 < NKS) r2_issue_wait<doff, 0>(pq[j + 1], pq[j + 1] + v_rel, rb[j + 1], rb[j]);
+      else r2_wait(rb[j]);
+      dp = mfma32(rb[j].f[0], rb[j].f[1], dp);
+    }
+  } else {                     // batches of two dO fragments against the V fragments held in registers
+    R2 rb[NKS / 2];
+    r2_issue<doff, doff>(pq[0], pq[1], rb[0]);
+#pragma unroll
+    for (int j = 0; j < NKS / 2; ++j) {
+      if (j + 1 < NKS / 2) r2_issue_wait<doff, doff>(pq[2 * j + 2], pq[2 * j + 3], rb[j + 1], rb[j]);
+      else r2_wait(rb[j]);
+      dp = mfma32(rb[j].f[0], vf[2 * j], dp);
+      dp = mfma32(rb[j].f[1], vf[2 * j + 1], dp);
+    }
+  }
 #pragma unroll
   for (int gq = 0; gq < 4; ++gq) {
     const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qb + 8 * gq + 4 * half]);
@@ -214,30 +260,36 @@ __device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const l
     }
   }
   const bf16x8 dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
-  // dV^T += dO^T P and dK^T += Q^T dS: transposed dO and Q fragments alternate in one stream
-  frag_pipeline<4 * NDB, kPreTr, 2, 1>(
-      [&](int i) {
-        const int off = qoff + ((i >> 1) & 1) * 16 * kRowBytes + ((i & 1) ? 0 : kTileBytes);
-        return lds_ld_tr(pqt[i >> 2][0], pqt[i >> 2][1], off);
-      },
-      [&](int i, bf16x8 f) {
-        const int db = i >> 2, ks = (i >> 1) & 1;
-        if (i & 1) dk[db] = mfma32(f, ks ? dsf1 : dsf0, dk[db]);
-        else dv[db] = mfma32(f, ks ? pf1 : pf0, dv[db]);
-      });
+  // dV^T += dO^T P and dK^T += Q^T dS.  Per head-dim block and 16-row step one batch of two
+  // transposed fragments (dO^T, Q^T); batch b = 2 * db + step.
+  Tr2 tb[2 * NDB];
+  constexpr int kQ0 = qoff, kQ1 = kQ0 + 16 * kRowBytes;
+  tr2_issue<kQ0 + kTileBytes, kQ0>(pqt[0][0], pqt[0][1], tb[0]);
+#pragma unroll
+  for (int b = 0; b < 2 * NDB; ++b) {
+    const int db = b >> 1;
+    if (b + 1 < 2 * NDB) {
+      if (b & 1) tr2_issue_wait<kQ0 + kTileBytes, kQ0>(pqt[db + 1][0], pqt[db + 1][1], tb[b + 1], tb[b]);
+      else tr2_issue_wait<kQ1 + kTileBytes, kQ1>(pqt[db][0], pqt[db][1], tb[b + 1], tb[b]);
+    } else {
+      tr2_wait(tb[b]);
+    }
+    dv[db] = mfma32(tr2_frag(tb[b], 0), (b & 1) ? pf1 : pf0, dv[db]);
+    dk[db] = mfma32(tr2_frag(tb[b], 1), (b & 1) ? dsf1 : dsf0, dk[db]);
+  }
 }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
-    const float* __restrict__ lse, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
+    const float* __restrict__ lse2, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
     int T, int Hq, int Hkv, float scale, int load_acc, int store_final) {
-  constexpr int NKS = D / 16, NDB = D / 32;
-  constexpr int kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes;
-  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes];   // [buffer][Q tile, dO tile]
-  __shared__ __attribute__((aligned(16))) float s_lse[2][kQStep];
-  __shared__ __attribute__((aligned(16))) float s_delta[2][kQStep];
+  constexpr int NKS = D / 16, NDB = D / 32, kQStep = DkdvCfg<D>::kQStep;
+  constexpr bool kVInLds = DkdvCfg<D>::kVInLds;
+  constexpr int kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes, kVBytes = kVInLds ? kKvOwn * D * 2 : 0;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes + kVBytes];   // [buffer][Q tile, dO tile], V tile
+  __shared__ __attribute__((aligned(16))) float s_stat[2][2][kQStep];             // [buffer][lse2, delta][row]
 
   const int g = Hq / Hkv;
   // one block per (key tile, kv head); kv heads of one tile adjacent, heavy tiles first
@@ -249,8 +301,8 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
   const int ld_key = min(my_key, T - 1);
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
-  // Flattened walk: for each run, for each head of the group, for each 64-row step.  Rows are
-  // addressed relative to the key tile's first row (every run of the item lies at or after it).
+  // Flattened walk: for each run, for each head of the group, for each step of kQStep rows.  Rows
+  // are addressed relative to the key tile's first row (every run of the item lies at or after it).
   int sgi = it.seg_begin, hh = 0;
   Seg sg = segs[sgi];
   int i0 = max(sg.q_lo, it.kv_row0);
@@ -258,20 +310,30 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
   const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
   const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
   const int head_bytes = D * 2;
+  float pre_stat = 0.f;                               // next step's lse2 (threads 0..kQStep-1) / delta (next kQStep)
+  // Row statistics first (through a register, written to LDS when the step ends), then the tiles
+  // straight into LDS buffer buf_.
 #define SLIMATTN_STAGE(buf_, row0_, head_)                                                                     \
   do {                                                                                                         \
+    if (tid < 2 * kQStep) {                                                                                    \
+      const int r_ = min((row0_) + (tid & (kQStep - 1)), T - 1);                                               \
+      pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)(head_) * T + r_];                                      \
+    }                                                                                                          \
     TileSource a_ = srcQ, b_ = srcDO;                                                                          \
     a_.voff += (head_) * head_bytes;                                                                           \
     b_.voff += (head_) * head_bytes;                                                                           \
     stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes, a_, (row0_) - it.kv_row0, tid);                       \
     stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes + kTileBytes, b_, (row0_) - it.kv_row0, tid);          \
-    if (tid < kQStep) {                                                                                        \
-      const int r_ = min((row0_) + tid, T - 1);                                                                \
-      s_lse[(buf_)][tid] = lse[(size_t)(head_) * T + r_] * kLog2e;                                             \
-      s_delta[(buf_)][tid] = delta[(size_t)(head_) * T + r_];                                                  \
-    }                                                                                                          \
+  } while (0)
+#define SLIMATTN_COMMIT(buf_)                                                                                  \
+  do {                                                                                                         \
+    if (tid < 2 * kQStep) (&s_stat[(buf_)][0][0])[tid] = pre_stat;                                             \
   } while (0)
   SLIMATTN_STAGE(0, i0, hk * g + hh);
+  if (kVInLds) {   // the block's 128 V rows, read as fragments by every step
+    const TileSource srcV = make_tile_source<D, 256>(v, it.kv_row0, Hkv, hk, T, tid);
+    stage_tile<D, kKvOwn, 256>(lds + 2 * kBufBytes, srcV, 0, tid);
+  }
 
   bf16x8 kf[NKS], vf[NKS];
   {
@@ -279,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       kf[ks] = scale8(*reinterpret_cast<const bf16x8*>(k + off + 16 * ks), scale * kLog2e);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
+      if (!kVInLds) vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
     }
   }
   lds_cptr pq[NKS], pqt[NDB][2];
@@ -287,48 +349,60 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
   for (int ks = 0; ks < NKS; ++ks) pq[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
 #pragma unroll
   for (int db = 0; db < NDB; ++db) lds_tr_ptrs<D>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
+  int v_rel = 2 * kBufBytes + wave * 32 * D * 2;      // the swizzle of row 32*wave + l32 equals that of row l32
   floatx16 dk[NDB], dv[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
+  SLIMATTN_COMMIT(0);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  int buf = 0;
-  while (have) {
-    const int cur_i0 = i0, cur_hi = sg.q_hi;
-    // advance to the next step (uniform across the block) and start fetching it
-    i0 += kQStep;
-    if (i0 >= sg.q_hi) {
-      if (++hh == g) {
-        hh = 0;
-        if (++sgi == it.seg_end) have = false; else sg = segs[sgi];
-      }
-      if (have) i0 = max(sg.q_lo, it.kv_row0);
-    }
-    if (have) SLIMATTN_STAGE(buf ^ 1, i0, hk * g + hh);
-
-    // local rows [rel_lo, rel_hi) minus 4*half contribute: row >= key and row < end of the run
-    const int rel_lo = my_key - cur_i0 - 4 * half, rel_hi = cur_hi - cur_i0 - 4 * half;
-#pragma unroll
-    for (int qb = 0; qb < kQStep / 32; ++qb) {
-      const int r0 = cur_i0 + 32 * qb;               // first row of the block
-      if (r0 + 31 < kv0w || r0 >= cur_hi) continue;  // wave-uniform: nothing at or after the wave's keys
-      if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)
-        dkdv_block<D, false>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, rel_lo, rel_hi, half);
-      else
-        dkdv_block<D, true>(pq, pqt, s_lse[buf], s_delta[buf], qb, kf, vf, dk, dv, rel_lo, rel_hi, half);
-    }
-    const int flip = buf ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) pq[ks] += flip;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) { pqt[db][0] += flip; pqt[db][1] += flip; }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    buf ^= 1;
+  // One step on buffer BUF_: advance the walk and start fetching the next step into the other
+  // buffer, multiply, publish the next step's row statistics, wait, barrier.
+#define SLIMATTN_QBLOCK(QB_, BUF_)                                                                             \
+  do {                                                                                                         \
+    const int r0 = cur_i0 + 32 * (QB_);            /* first row of the block */                                \
+    if (!(r0 + 31 < kv0w || r0 >= cur_hi)) {       /* wave-uniform: something at or after the wave's keys */   \
+      if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)                                                                \
+        dkdv_block<D, false, QB_, BUF_>(pq, pqt, v_rel, s_stat[BUF_][0], s_stat[BUF_][1], kf, vf, dk, dv, rel_lo, \
+                                        rel_hi, half);                                                         \
+      else                                                                                                     \
+        dkdv_block<D, true, QB_, BUF_>(pq, pqt, v_rel, s_stat[BUF_][0], s_stat[BUF_][1], kf, vf, dk, dv, rel_lo, \
+                                       rel_hi, half);                                                          \
+    }                                                                                                          \
+  } while (0)
+#define SLIMATTN_STEP(BUF_)                                                                                    \
+  do {                                                                                                         \
+    const int cur_i0 = i0, cur_hi = sg.q_hi;                                                                   \
+    i0 += kQStep;                                                                                              \
+    if (i0 >= sg.q_hi) {                                                                                       \
+      if (++hh == g) {                                                                                         \
+        hh = 0;                                                                                                \
+        if (++sgi == it.seg_end) have = false; else sg = segs[sgi];                                            \
+      }                                                                                                        \
+      if (have) i0 = max(sg.q_lo, it.kv_row0);                                                                 \
+    }                                                                                                          \
+    if (have) SLIMATTN_STAGE((BUF_) ^ 1, i0, hk * g + hh);                                                     \
+    asm volatile("" : "+v"(v_rel));                /* keep the V fragment addresses from being hoisted */     \
+    /* local rows [rel_lo, rel_hi) minus 4*half contribute: row >= key and row < end of the run */           \
+    const int rel_lo = my_key - cur_i0 - 4 * half, rel_hi = cur_hi - cur_i0 - 4 * half;                        \
+    SLIMATTN_QBLOCK(0, BUF_);                                                                                  \
+    if (kQStep == 64) SLIMATTN_QBLOCK(kQStep == 64 ? 1 : 0, BUF_);                                             \
+    if (have) SLIMATTN_COMMIT((BUF_) ^ 1);                                                                     \
+    __builtin_amdgcn_s_waitcnt(0);                                                                             \
+    __syncthreads();                                                                                           \
+  } while (0)
+  while (true) {                                      // `have` is uniform across the block
+    SLIMATTN_STEP(0);
+    if (!have) break;
+    SLIMATTN_STEP(1);
+    if (!have) break;
   }
+#undef SLIMATTN_STEP
+#undef SLIMATTN_QBLOCK
+#undef SLIMATTN_COMMIT
 #undef SLIMATTN_STAGE
 
   if (my_key < kv_end) {
@@ -376,17 +450,17 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
 int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kKvOwn; }
 
-int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, float* delta) {
+int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2) {
   const slimattn_params& p = *c.p;
   const int64_t n = c.T * p.n_q_heads * (p.head_dim / 8);
   if (n == 0) return 0;
   const dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (p.head_dim == 128)
-    hipLaunchKernelGGL(delta_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, delta,
-                       (int)c.T, p.n_q_heads);
+    hipLaunchKernelGGL(delta_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse, delta,
+                       lse2, (int)c.T, p.n_q_heads);
   else
-    hipLaunchKernelGGL(delta_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, delta,
-                       (int)c.T, p.n_q_heads);
+    hipLaunchKernelGGL(delta_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse, delta,
+                       lse2, (int)c.T, p.n_q_heads);
   return (int)hipGetLastError();
 }
 

@@ -34,10 +34,10 @@ constexpr float kLazy = 8.f;  // rescale the accumulators only when a row maximu
 // at minus the row's reference maximum m_ref, so they come out as the exponents directly.
 __device__ __forceinline__ int fbits(float x) { return __builtin_bit_cast(int, x); }
 
-template <int D, bool MASKED>
+template <int D, bool MASKED, class Side>
 __device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pv)[D / 32][2],
                                          const bf16x8 (&qf)[D / 16], floatx16 (&oacc)[D / 32], float& m_ref, float& l_run,
-                                         int rel) {
+                                         int rel, Side&& side) {
   constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2;
   floatx16 sacc[2];
 #pragma unroll
@@ -45,8 +45,9 @@ __device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[b][r] = -m_ref;
   // S^T = K Q^T (minus the reference maximum)
-  frag_pipeline<2 * NKS, 4, 1, 1>([&](int i) { return lds_ld_row(pk[i % NKS], (i / NKS) * 32 * kRowBytes); },
-                                  [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); });
+  // (the next tile's global->LDS loads are issued one at a time between the products)
+  frag_pipeline_side<2 * NKS, 4>([&](int i) { return lds_ld_row(pk[i % NKS], (i / NKS) * 32 * kRowBytes); },
+                                 [&](int i, bf16x8 f) { sacc[i / NKS] = mfma32(f, qf[i % NKS], sacc[i / NKS]); }, side);
   if (MASKED) {      // key (j0 + 32b + 8(r/4) + 4 half + r%4) > row  <=>  32b + 8(r/4) + r%4 > rel
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -99,9 +100,17 @@ __device__ __forceinline__ void fwd_tile(const lds_cptr (&pk)[D / 16], const lds
     ps[ks2] = sum8(pf[ks2], ps[ks2]);             // row sum of the rounded probabilities the product uses
   }
   l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
-  // O^T += V^T P^T
-  frag_pipeline<4 * NDB, 4, 2, 1>([&](int i) { return lds_ld_tr(pv[i >> 2][0], pv[i >> 2][1], (i & 3) * 16 * kRowBytes); },
-                                  [&](int i, bf16x8 f) { oacc[i >> 2] = mfma32(f, pf[i & 3], oacc[i >> 2]); });
+  // O^T += V^T P^T: one batch of four V^T fragments (the four 16-key steps) per head-dim block
+  Tr4 tb[NDB];
+  constexpr int kStep = 16 * kRowBytes;
+  tr4_issue<0, kStep, 2 * kStep, 3 * kStep>(pv[0][0], pv[0][1], tb[0]);
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    if (db + 1 < NDB) tr4_issue_wait<0, kStep, 2 * kStep, 3 * kStep>(pv[db + 1][0], pv[db + 1][1], tb[db + 1], tb[db]);
+    else tr4_wait(tb[db]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) oacc[db] = mfma32(tr4_frag(tb[db], j), pf[j], oacc[db]);
+  }
 }
 
 template <int D>
@@ -164,16 +173,23 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kFwdBK;
-    // next tile straight into the other buffer (its last readers passed the barrier below);
-    // past the end of the tensor the loads return zeros that nobody uses
+    // next tile straight into the other buffer (its last readers passed the barrier below); past
+    // the end of the tensor the loads return zeros that nobody uses.  kPasses loads per tensor,
+    // spread over the first products of the tile.
     const int nb = ((t + 1) & 1) * kBufBytes;
-    stage_tile<D, kFwdBK, 256>(lds + nb, srcK, (t + 1) * kFwdBK, tid);
-    stage_tile<D, kFwdBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kFwdBK, tid);
+    constexpr int kPasses = kFwdBK * D * 2 / 256 / 16;
+    auto side = [&](int i) {
+      if (i < kPasses) stage_pass<D, 256>(lds + nb, srcK, (t + 1) * kFwdBK, i, tid);
+      else if (i < 2 * kPasses) stage_pass<D, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kFwdBK, i - kPasses, tid);
+    };
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kFwdBK - 1 <= q0w) {                  // whole tile visible to every row of the wave
-      fwd_tile<D, false>(pk, pv, qf, oacc, m_ref, l_run, rel);
+      fwd_tile<D, false>(pk, pv, qf, oacc, m_ref, l_run, rel, side);
     } else if (j0 <= q0w + 31) {                   // diagonal region
-      fwd_tile<D, true>(pk, pv, qf, oacc, m_ref, l_run, rel);
+      fwd_tile<D, true>(pk, pv, qf, oacc, m_ref, l_run, rel, side);
+    } else {                                       // nothing visible to this wave: only fetch
+#pragma unroll
+      for (int i = 0; i < 2 * kPasses; ++i) side(i);
     }
     const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
 #pragma unroll

@@ -80,10 +80,11 @@ int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
 
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
-int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, float* delta);
-int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, float* delta, float* lse2);
+// the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
+int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                        const float* delta, void* dQ, const QItem* items, int n_items);
-int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
                          int n_items, const Seg* segs, int load_acc, int store_final);
 int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);

@@ -96,13 +96,15 @@ __device__ __forceinline__ float sum8(bf16x8 a, float acc) {
   return acc;
 }
 
+struct FragPair { bf16x8 a, b; };
+
 // Software-pipelined operand stream: N fragments, each read from LDS kPre steps before the
 // product that consumes it.  `load(i)` returns fragment i, `use(i, frag)` issues its products.
 // The trailing scheduling directives pin the order "kPre reads, then (products, read) ...";
 // rpf = LDS read instructions per fragment, upf = products per fragment.
 template <int N, int kPre, int rpf, int upf, class Load, class Use>
 __device__ __forceinline__ void frag_pipeline(Load&& load, Use&& use) {
-  bf16x8 fr[N];
+  decltype(load(0)) fr[N];
 #pragma unroll
   for (int i = 0; i < N + kPre; ++i) {
     if (i < N) fr[i] = load(i);
@@ -113,62 +115,6 @@ __device__ __forceinline__ void frag_pipeline(Load&& load, Use&& use) {
   for (int i = 0; i < N; ++i) {
     __builtin_amdgcn_sched_group_barrier(0x008, upf, 0);
     if (i + kPre < N) __builtin_amdgcn_sched_group_barrier(0x100, rpf, 0);
-  }
-}
-
-// Stage ROWS x D bf16 rows [row0, row0+ROWS) of head h of a [T, H, D] tensor: global -> registers.
-// Rows past T-1 are clamped (their values are never used unmasked).
-template <int D, int ROWS, int NT>
-struct TileStage {
-  static constexpr int kChunks = ROWS * D / 8 / NT;     // 16-byte chunks per thread
-  static_assert(ROWS * D / 8 % NT == 0, "tile must divide evenly over the block");
-  uint4 r[kChunks];
-  __device__ __forceinline__ void load(const bf16* __restrict__ base, int row0, int H, int h, int T, int tid) {
-#pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int c = tid + NT * i, row = c / (D / 8), u = c % (D / 8);
-      const int gr = min(row0 + row, T - 1);
-      r[i] = *reinterpret_cast<const uint4*>(base + ((size_t)gr * H + h) * D + u * 8);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int c = tid + NT * i, row = c / (D / 8), u = c % (D / 8);
-      *reinterpret_cast<uint4*>(tile + lds_off16<D>(row, u)) = r[i];
-    }
-  }
-};
-
-// Direct global -> LDS staging of a ROWS x D bf16 tile (rows [row0, row0+ROWS) of head h of a
-// [T, H, D] tensor) in the swizzled layout above, without passing through registers: each wave
-// issues 16-byte-per-lane loads whose LDS destination is 1 KiB contiguous (wave-uniform base +
-// lane * 16), so the lane that lands on LDS unit position p of a 256-byte line fetches the global
-// chunk that the swizzle maps to p.  Rows past T-1 are clamped.  Completion: vmcnt, then a barrier.
-template <int D, int ROWS, int NT>
-__device__ __forceinline__ void stage_tile_direct(char* tile, const bf16* __restrict__ base, int row0, int H, int h, int T,
-                                                  int tid) {
-  constexpr int kLines = ROWS * D * 2 / 256;          // 256-byte lines in the tile
-  constexpr int kLinesPerPass = NT / 16;              // 16 lanes per line
-  static_assert(kLines % kLinesPerPass == 0, "tile must divide evenly over the block");
-  const int wave_line0 = (tid >> 6) * 4, lane = tid & 63;
-#pragma unroll
-  for (int i = 0; i < kLines / kLinesPerPass; ++i) {
-    const int line = i * kLinesPerPass + wave_line0 + (lane >> 4), pos = lane & 15;
-    int row, chunk;
-    if (D == 128) {
-      row = line;
-      chunk = pos ^ (((row & 3) << 2) | ((row >> 2) & 3));
-    } else {
-      const int u = pos ^ (((line & 1) << 2) | ((line >> 1) & 3));
-      row = 2 * line + (u >> 3);
-      chunk = u & 7;
-    }
-    const int gr = min(row0 + row, T - 1);
-    const bf16* src = base + ((size_t)gr * H + h) * D + chunk * 8;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(tile + (i * kLinesPerPass + wave_line0) * 256),
-                                     16, 0, 0);
   }
 }
 
@@ -207,6 +153,127 @@ __device__ __forceinline__ bf16x8 lds_ld_tr(lds_cptr p0, lds_cptr p1, int byte_o
   short8v r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, r);
 }
+
+// ---- transposed fragment stream through inline asm ---------------------------------------------
+// The compiler's wait-count insertion treats an LDS transpose load as possibly reading what an
+// outstanding direct global->LDS load is still writing and puts a full vmcnt(0) wait in front of
+// it, which would serialise each tile behind the prefetch of the next one.  The prefetch targets
+// the other buffer, so the transpose loads are issued from inline asm, in batches of four
+// fragments (eight loads), with the wait counts written by hand: a batch is issued, then
+// lgkmcnt(8) waits for everything older than it -- LDS operations complete in order -- which
+// makes the previous batch ready while this one is still in flight.  The previous batch is
+// passed through the asm as an in/out operand so that its consumers are ordered after the wait.
+struct Tr4 { short4v r[8]; };     // four fragments; fragment j = (r[2j], r[2j+1])
+
+__device__ __forceinline__ bf16x8 tr4_frag(const Tr4& t, int j) {
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+  short8v x = __builtin_shufflevector(t.r[2 * j], t.r[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, x);
+}
+#define SLIMATTN_TR4_READS                                   \
+  "ds_read_b64_tr_b16 %0, %[p0] offset:%[o0]\n\t"            \
+  "ds_read_b64_tr_b16 %1, %[p1] offset:%[o0]\n\t"            \
+  "ds_read_b64_tr_b16 %2, %[p0] offset:%[o1]\n\t"            \
+  "ds_read_b64_tr_b16 %3, %[p1] offset:%[o1]\n\t"            \
+  "ds_read_b64_tr_b16 %4, %[p0] offset:%[o2]\n\t"            \
+  "ds_read_b64_tr_b16 %5, %[p1] offset:%[o2]\n\t"            \
+  "ds_read_b64_tr_b16 %6, %[p0] offset:%[o3]\n\t"            \
+  "ds_read_b64_tr_b16 %7, %[p1] offset:%[o3]\n\t"
+// Issue the four fragments at byte offsets O0..O3 from the fragment address pair (p0, p1).
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void tr4_issue(lds_cptr p0, lds_cptr p1, Tr4& n) {
+  asm volatile(SLIMATTN_TR4_READS
+               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3]), "=&v"(n.r[4]), "=&v"(n.r[5]), "=&v"(n.r[6]),
+                 "=&v"(n.r[7])
+               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2), [o3] "n"(O3));
+}
+// Issue the next batch, then wait until the previous batch `p` has landed.
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void tr4_issue_wait(lds_cptr p0, lds_cptr p1, Tr4& n, Tr4& p) {
+  asm volatile(SLIMATTN_TR4_READS "s_waitcnt lgkmcnt(8)"
+               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3]), "=&v"(n.r[4]), "=&v"(n.r[5]), "=&v"(n.r[6]),
+                 "=&v"(n.r[7]), "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]), "+v"(p.r[4]), "+v"(p.r[5]),
+                 "+v"(p.r[6]), "+v"(p.r[7])
+               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2), [o3] "n"(O3));
+}
+// Wait until batch `p` (the last one issued) has landed.
+__device__ __forceinline__ void tr4_wait(Tr4& p) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]), "+v"(p.r[4]), "+v"(p.r[5]), "+v"(p.r[6]),
+                 "+v"(p.r[7]));
+}
+
+// Two-fragment variant (four loads per batch) for kernels that are short of registers.
+struct Tr2 { short4v r[4]; };
+__device__ __forceinline__ bf16x8 tr2_frag(const Tr2& t, int j) {
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+  short8v x = __builtin_shufflevector(t.r[2 * j], t.r[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, x);
+}
+#define SLIMATTN_TR2_READS                                   \
+  "ds_read_b64_tr_b16 %0, %[p0] offset:%[o0]\n\t"            \
+  "ds_read_b64_tr_b16 %1, %[p1] offset:%[o0]\n\t"            \
+  "ds_read_b64_tr_b16 %2, %[p0] offset:%[o1]\n\t"            \
+  "ds_read_b64_tr_b16 %3, %[p1] offset:%[o1]\n\t"
+template <int O0, int O1>
+__device__ __forceinline__ void tr2_issue(lds_cptr p0, lds_cptr p1, Tr2& n) {
+  asm volatile(SLIMATTN_TR2_READS
+               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3])
+               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1));
+}
+template <int O0, int O1>
+__device__ __forceinline__ void tr2_issue_wait(lds_cptr p0, lds_cptr p1, Tr2& n, Tr2& p) {
+  asm volatile(SLIMATTN_TR2_READS "s_waitcnt lgkmcnt(4)"
+               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3]), "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]),
+                 "+v"(p.r[3])
+               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1));
+}
+__device__ __forceinline__ void tr2_wait(Tr2& p) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]));
+}
+
+// Row-fragment batches through inline asm (same reason and same protocol as the transposed ones):
+// four 16-byte fragment loads per batch, each with its own address register and byte offset.
+struct R4 { bf16x8 f[4]; };
+#define SLIMATTN_R4_READS                               \
+  "ds_read_b128 %0, %[a0] offset:%[o0]\n\t"             \
+  "ds_read_b128 %1, %[a1] offset:%[o1]\n\t"             \
+  "ds_read_b128 %2, %[a2] offset:%[o2]\n\t"             \
+  "ds_read_b128 %3, %[a3] offset:%[o3]\n\t"
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void r4_issue(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n) {
+  asm volatile(SLIMATTN_R4_READS
+               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3])
+               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
+                 [o3] "n"(O3));
+}
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void r4_issue_wait(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n, R4& p) {
+  asm volatile(SLIMATTN_R4_READS "s_waitcnt lgkmcnt(4)"
+               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3]), "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]),
+                 "+v"(p.f[3])
+               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
+                 [o3] "n"(O3));
+}
+__device__ __forceinline__ void r4_wait(R4& p) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]), "+v"(p.f[3]));
+}
+
+// Two-fragment row batches for kernels that are short of registers.
+struct R2 { bf16x8 f[2]; };
+template <int O0, int O1>
+__device__ __forceinline__ void r2_issue(lds_cptr a0, lds_cptr a1, R2& n) {
+  asm volatile("ds_read_b128 %0, %[a0] offset:%[o0]\n\tds_read_b128 %1, %[a1] offset:%[o1]"
+               : "=&v"(n.f[0]), "=&v"(n.f[1])
+               : [a0] "v"(a0), [a1] "v"(a1), [o0] "n"(O0), [o1] "n"(O1));
+}
+template <int O0, int O1>
+__device__ __forceinline__ void r2_issue_wait(lds_cptr a0, lds_cptr a1, R2& n, R2& p) {
+  asm volatile("ds_read_b128 %0, %[a0] offset:%[o0]\n\tds_read_b128 %1, %[a1] offset:%[o1]\n\ts_waitcnt lgkmcnt(2)"
+               : "=&v"(n.f[0]), "=&v"(n.f[1]), "+v"(p.f[0]), "+v"(p.f[1])
+               : [a0] "v"(a0), [a1] "v"(a1), [o0] "n"(O0), [o1] "n"(O1));
+}
+__device__ __forceinline__ void r2_wait(R2& p) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.f[0]), "+v"(p.f[1])); }
 
 // ---- global -> LDS staging through buffer loads -----------------------------------------------
 // A TileSource addresses the rows of one head of a [T, H, D] bf16 tensor starting at row `row_base`
@@ -247,11 +314,41 @@ template <int D, int ROWS, int NT>
 __device__ __forceinline__ void stage_tile(LDS_PTR(char) tile, const TileSource& s, int row0, int tid) {
   constexpr int kLines = ROWS * D * 2 / 256, kLinesPerPass = NT / 16, kRowsPerPass = kLinesPerPass * 256 / (D * 2);
   static_assert(kLines % kLinesPerPass == 0, "tile must divide evenly over the block");
-  const int wave_line0 = (tid >> 6) * 4;
+  const int wave_off = __builtin_amdgcn_readfirstlane((tid >> 6) * 1024);   // wave-uniform by construction
 #pragma unroll
   for (int i = 0; i < kLines / kLinesPerPass; ++i)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, tile + (i * kLinesPerPass + wave_line0) * 256, 16, s.voff,
-                                             (row0 + i * kRowsPerPass) * s.row_bytes, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, tile + i * kLinesPerPass * 256 + wave_off, 16, s.voff,
+                                             __builtin_amdgcn_readfirstlane((row0 + i * kRowsPerPass) * s.row_bytes), 0, 0);
+}
+
+// One pass (NT / 16 lines of 256 bytes) of stage_tile: pass i of the tile at row offset row0.
+template <int D, int NT>
+__device__ __forceinline__ void stage_pass(LDS_PTR(char) tile, const TileSource& s, int row0, int i, int tid) {
+  constexpr int kLinesPerPass = NT / 16, kRowsPerPass = kLinesPerPass * 256 / (D * 2);
+  const int wave_off = __builtin_amdgcn_readfirstlane((tid >> 6) * 1024);   // wave-uniform by construction
+  const int soff = __builtin_amdgcn_readfirstlane((row0 + i * kRowsPerPass) * s.row_bytes);   // uniform as well
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, tile + i * kLinesPerPass * 256 + wave_off, 16, s.voff, soff, 0, 0);
+}
+
+// frag_pipeline with one extra action per fragment (`side(i)`, e.g. one global->LDS load) issued
+// alongside the products, so that the loads are spread over the phase instead of bunched.
+template <int N, int kPre, class Load, class Use, class Side>
+__device__ __forceinline__ void frag_pipeline_side(Load&& load, Use&& use, Side&& side) {
+  decltype(load(0)) fr[N];
+#pragma unroll
+  for (int i = 0; i < N + kPre; ++i) {
+    if (i < N) fr[i] = load(i);
+    if (i >= kPre) {
+      use(i - kPre, fr[i - kPre]);
+      side(i - kPre);
+    }
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, kPre, 0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (i + kPre < N) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
 }
 
 __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {

@@ -199,7 +199,7 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_t hkv, int32_t d) {
   if (!t || hq < 1 || hkv < 1 || d < 1) return 0;
   const size_t T = (size_t)t->total_tokens;
-  return align_up(2 * T * hkv * d * sizeof(float)) + align_up(T * hq * sizeof(float)) + 256;
+  return align_up(2 * T * hkv * d * sizeof(float)) + 2 * align_up(T * hq * sizeof(float)) + 256;
 }
 
 }  // extern "C"
