@@ -102,6 +102,12 @@ def main():
         p.forward(flags=flags)
         p.backward(flags=flags)
 
+    # A plain device copy of known size (256 MiB read + 256 MiB written) before anything else: under
+    # `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` it calibrates the counters' units for roofline.traffic.
+    cal = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+    cal2 = torch.empty_like(cal)
+    cal2.copy_(cal)
+    del cal, cal2
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

@@ -301,11 +301,16 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
   const int ld_key = min(my_key, T - 1);
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
-  // Flattened walk: for each run, for each head of the group, for each step of kQStep rows.  Rows
-  // are addressed relative to the key tile's first row (every run of the item lies at or after it).
-  int sgi = it.seg_begin, hh = 0;
+  // Flattened walk: runs from the last to the first, inside a run steps of kQStep rows from the top
+  // down, inside a step the heads of the group.  Every key tile of a sample thus starts at the
+  // sample's last rows and moves towards its own rows, so the blocks that run side by side read the
+  // same Q/dO rows at about the same time and share them through L2.  Steps are aligned to the
+  // tile's first row; rows are addressed relative to it (every run of the item lies at or after it).
+  int sgi = it.seg_end - 1, hh = 0;
   Seg sg = segs[sgi];
-  int i0 = max(sg.q_lo, it.kv_row0);
+  int lo = max(sg.q_lo, it.kv_row0);
+  int n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
+  int i0 = lo + n * kQStep;
   bool have = true;                                   // a key tile always has at least its own rows
   const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
   const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
@@ -376,13 +381,18 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
 #define SLIMATTN_STEP(BUF_)                                                                                    \
   do {                                                                                                         \
     const int cur_i0 = i0, cur_hi = sg.q_hi;                                                                   \
-    i0 += kQStep;                                                                                              \
-    if (i0 >= sg.q_hi) {                                                                                       \
-      if (++hh == g) {                                                                                         \
-        hh = 0;                                                                                                \
-        if (++sgi == it.seg_end) have = false; else sg = segs[sgi];                                            \
+    if (++hh == g) {                                                                                           \
+      hh = 0;                                                                                                  \
+      if (--n < 0) {                                                                                           \
+        if (--sgi < it.seg_begin) {                                                                            \
+          have = false;                                                                                        \
+        } else {                                                                                               \
+          sg = segs[sgi];                                                                                      \
+          lo = max(sg.q_lo, it.kv_row0);                                                                       \
+          n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;                                                        \
+        }                                                                                                      \
       }                                                                                                        \
-      if (have) i0 = max(sg.q_lo, it.kv_row0);                                                                 \
+      i0 = lo + n * kQStep;                                                                                    \
     }                                                                                                          \
     if (have) SLIMATTN_STAGE((BUF_) ^ 1, i0, hk * g + hh);                                                     \
     asm volatile("" : "+v"(v_rel));                /* keep the V fragment addresses from being hoisted */     \
