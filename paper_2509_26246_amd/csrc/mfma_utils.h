@@ -228,6 +228,17 @@ __device__ __forceinline__ void tr2_issue_wait(lds_cptr p0, lds_cptr p1, Tr2& n,
                  "+v"(p.r[3])
                : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1));
 }
+// Two fragments from two different address pairs at one byte offset (e.g. the same key step of two
+// head-dim blocks, which feed two independent accumulators).
+template <int O>
+__device__ __forceinline__ void tr2x_issue(lds_cptr a0, lds_cptr a1, lds_cptr b0, lds_cptr b1, Tr2& n) {
+  asm volatile("ds_read_b64_tr_b16 %0, %[a0] offset:%[o]\n\t"
+               "ds_read_b64_tr_b16 %1, %[a1] offset:%[o]\n\t"
+               "ds_read_b64_tr_b16 %2, %[b0] offset:%[o]\n\t"
+               "ds_read_b64_tr_b16 %3, %[b1] offset:%[o]"
+               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3])
+               : [a0] "v"(a0), [a1] "v"(a1), [b0] "v"(b0), [b1] "v"(b1), [o] "n"(O));
+}
 __device__ __forceinline__ void tr2_wait(Tr2& p) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]));
 }
@@ -274,6 +285,31 @@ __device__ __forceinline__ void r2_issue_wait(lds_cptr a0, lds_cptr a1, R2& n, R
                : [a0] "v"(a0), [a1] "v"(a1), [o0] "n"(O0), [o1] "n"(O1));
 }
 __device__ __forceinline__ void r2_wait(R2& p) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.f[0]), "+v"(p.f[1])); }
+
+// Wait until at most N LDS operations issued by this wave are outstanding; `p` (a batch issued
+// before those N) is then complete, and its consumers are ordered after the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait(R4& p) {
+  asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]), "+v"(p.f[3]) : [n] "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(R2& p) {
+  asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]) : [n] "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(Tr2& p) {
+  asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]) : [n] "n"(N));
+}
+
+// Compile-time loop: f(IC<0>{}), ..., f(IC<N-1>{}).
+template <int I> struct IC { static constexpr int value = I; constexpr operator int() const { return I; } };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 // ---- global -> LDS staging through buffer loads -----------------------------------------------
 // A TileSource addresses the rows of one head of a [T, H, D] bf16 tensor starting at row `row_base`
