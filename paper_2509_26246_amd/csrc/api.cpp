@@ -111,6 +111,8 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   float* acc_dv = acc_dk + acc_elems;
   float* delta = (float*)((char*)workspace + align_up(2 * acc_elems * sizeof(float)));
   float* lse2 = (float*)((char*)delta + align_up(T * p->n_q_heads * sizeof(float)));   // bf16 path: lse in log2 units
+  float* parts = (float*)((char*)lse2 + align_up(T * p->n_q_heads * sizeof(float)));  // partial tiles of divided key tiles
+  const int sc = split_class(p->n_kv_heads);
   const LaunchCtx ctx{p, stream, t->total_tokens};
   const int n_units = t->n_units[1];
   const bool whole = lo == 0 && hi == n_units;
@@ -138,14 +140,27 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
                                        delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
                                        store_final)
                  : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
-                                        store_final);
+                                        store_final, parts);
+    });
+  };
+  // bf16: the key-tile list in which heavy tiles are divided among several blocks, followed by the
+  // launch that adds the parts up (a scope without divided tiles has an empty reduction list)
+  auto run_dkdv_split = [&](const ScopeLists& L, const DeviceLists& D, int u, int load_acc, int store_final) -> int {
+    const int a = L.split_off[sc][u], b = L.split_off[sc][u + 1];
+    int e = run_dkdv(D.split_items[sc] + a, b - a, D.segs, load_acc, store_final);
+    if (e != 0) return e;
+    const int ra = L.reduce_off[sc][u], rb = L.reduce_off[sc][u + 1];
+    if (rb == ra) return 0;
+    return timed(SLIMATTN_K_FINALIZE, stream, [&] {
+      return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[sc] + ra, rb - ra, load_acc, store_final);
     });
   };
 
   if (whole && !per_unit) {
     // One scope holding every slice: each key tile's owner sums all later query rows itself and
     // writes dK/dV directly; the fp32 accumulators in the workspace are not touched.
-    rc = hip_rc(run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1));
+    rc = hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1)
+                    : run_dkdv_split(t->fused, t->d_fused, 0, 0, 1));
     if (rc != SLIMATTN_OK) return rc;
     return hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
   }
@@ -164,7 +179,8 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     // Units run one after another on the stream; each adds its queries' contributions to the
     // accumulators of every key tile of the prefix it sees (read-modify-write by the tile's
     // single owner), so the summation order is the unit order.
-    rc = hip_rc(run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0));
+    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0)
+                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u, 1, 0));
     if (rc != SLIMATTN_OK) return rc;
     if (per_unit) {
       rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));

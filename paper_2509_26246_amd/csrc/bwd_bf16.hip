@@ -22,6 +22,7 @@ namespace {
 
 constexpr int kDqBQ = 128, kDqBK = 64;
 constexpr int kKvOwn = 128;
+static_assert(kKvOwn == kSplitTileRows, "divided key-tile lists are built for this tile");
 // query rows per step of the dK/dV walk: at head_dim 128 the wave's V fragments live in LDS and the
 // step is 32 rows, which keeps the kernel at two waves per SIMD without register spills
 template <int D> struct DkdvCfg { static constexpr int kQStep = D == 128 ? 32 : 64; static constexpr bool kVInLds = D == 128; };
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const float* __restrict__ lse2, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
-    int T, int Hq, int Hkv, float scale, int load_acc, int store_final) {
+    int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
   constexpr int NKS = D / 16, NDB = D / 32, kQStep = DkdvCfg<D>::kQStep;
   constexpr bool kVInLds = DkdvCfg<D>::kVInLds;
   constexpr int kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes, kVBytes = kVInLds ? kKvOwn * D * 2 : 0;
@@ -415,7 +416,22 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
 #undef SLIMATTN_COMMIT
 #undef SLIMATTN_STAGE
 
-  if (my_key < kv_end) {
+  if (it.slot >= 0) {
+    // one part of a divided key tile: fp32 partial tile [slot][kv head][dK, dV][128 rows][D]
+    float* pk_ = parts + ((size_t)it.slot * Hkv + hk) * (2 * kKvOwn * D) + (size_t)(32 * wave + l32) * D;
+    float* pv_ = pk_ + kKvOwn * D;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const int off = 32 * db + 8 * gq + 4 * half;
+        floatx4 a, b;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) { a[x] = dk[db][4 * gq + x] * scale; b[x] = dv[db][4 * gq + x]; }
+        *reinterpret_cast<floatx4*>(pk_ + off) = a;
+        *reinterpret_cast<floatx4*>(pv_ + off) = b;
+      }
+  } else if (my_key < kv_end) {
     const size_t base = ((size_t)my_key * Hkv + hk) * D;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -442,6 +458,37 @@ __global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
           *reinterpret_cast<floatx4*>(acc_dv + off) = b;
         }
       }
+  }
+}
+
+// Sum of the partial tiles of a divided key tile, in slot order (fixed, so the result does not
+// depend on which block finished first), added to the fp32 accumulators or written as bf16.
+// One block per (tile, kv head); a thread owns four consecutive columns of a row.
+template <int D>
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ parts, float* __restrict__ acc_dk,
+                                                           float* __restrict__ acc_dv, bf16* __restrict__ dK,
+                                                           bf16* __restrict__ dV, const KvReduce* __restrict__ items,
+                                                           int Hkv, int load_acc, int store_final) {
+  const KvReduce it = items[blockIdx.x / Hkv];
+  const int hk = blockIdx.x % Hkv;
+  constexpr int kTile = kKvOwn * D;
+  for (int e = threadIdx.x * 4; e < 2 * kTile; e += 256 * 4) {
+    const int which = e / kTile, r = (e % kTile) / D, c = e % D;
+    if (r >= it.kv_rows) continue;
+    floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < it.n_parts; ++p)
+      sum += *reinterpret_cast<const floatx4*>(parts + ((size_t)(it.first_slot + p) * Hkv + hk) * (2 * kTile) + e);
+    const size_t off = ((size_t)(it.kv_row0 + r) * Hkv + hk) * D + c;
+    float* acc = which ? acc_dv : acc_dk;
+    if (load_acc) sum += *reinterpret_cast<const floatx4*>(acc + off);
+    if (store_final) {
+      bf16x4 w;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) w[x] = (bf16)sum[x];
+      *reinterpret_cast<bf16x4*>((which ? dV : dK) + off) = w;
+    } else {
+      *reinterpret_cast<floatx4*>(acc + off) = sum;
+    }
   }
 }
 
@@ -493,18 +540,32 @@ int launch_bwd_dq_bf16(const LaunchCtx& c, const void* q, const void* k, const v
 
 int launch_bwd_dkdv_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                         int n_items, const Seg* segs, int load_acc, int store_final) {
+                         int n_items, const Seg* segs, int load_acc, int store_final, float* parts) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(dkdv_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final);
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
   else
     hipLaunchKernelGGL(dkdv_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final);
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+  return (int)hipGetLastError();
+}
+
+int launch_bwd_reduce_bf16(const LaunchCtx& c, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
+                           const KvReduce* items, int n_items, int load_acc, int store_final) {
+  if (n_items == 0) return 0;
+  const slimattn_params& p = *c.p;
+  const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(reduce_parts_kernel<128>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
+                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final);
+  else
+    hipLaunchKernelGGL(reduce_parts_kernel<64>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
+                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final);
   return (int)hipGetLastError();
 }
 

@@ -23,8 +23,21 @@ struct QItem { int32_t q_row0, q_rows, kv_start, pad; };
 struct Seg { int32_t q_lo, q_hi; };
 
 // A key tile: rows [kv_row0, kv_row0 + kv_rows) of one sample, and the scope's query runs of that
-// sample that end after kv_row0 (segs[seg_begin .. seg_end), ascending).
-struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end; };
+// sample that end after kv_row0 (segs[seg_begin .. seg_end), ascending).  slot < 0: the item covers
+// every such run and its block owns the tile's dK/dV.  slot >= 0: the item is one part of a heavy
+// tile whose query rows were divided among several blocks; it covers only its own runs and stores
+// its sums as fp32 partial tile number `slot`, which a reduction launch adds up in slot order.
+struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end, slot, pad0, pad1, pad2; };
+
+// A divided key tile: partial tiles first_slot .. first_slot + n_parts - 1 are its parts.
+struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts; };
+
+// Divided lists exist for the 128-row key tile and four classes of KV-head count (1, 2, 4, >= 8):
+// a launch has items x KV heads blocks, so the fewer KV heads, the fewer blocks share the work and
+// the more a single long sample's first tiles dominate the makespan.
+constexpr int kSplitTileRows = 128;
+constexpr int kNumSplitClasses = 4;
+inline int split_class(int n_kv_heads) { return n_kv_heads >= 8 ? 3 : n_kv_heads >= 4 ? 2 : n_kv_heads >= 2 ? 1 : 0; }
 
 // A launch scope is either one unit or the whole list ("fused").  Its items are stored heavy-first.
 struct ScopeLists {
@@ -32,13 +45,21 @@ struct ScopeLists {
   std::vector<QItem> q_items[kNumTileSizes];    // unit-major, each unit heavy-first
   std::vector<int32_t> kv_off[kNumTileSizes];
   std::vector<KvItem> kv_items[kNumTileSizes];
-  std::vector<Seg> segs;                        // all units' runs, referenced by kv_items
+  std::vector<Seg> segs;                        // all units' runs (and the parts' cut runs), referenced by the items
+  // 128-row key tiles with heavy tiles divided, per KV-head class; same unit-major layout
+  std::vector<int32_t> split_off[kNumSplitClasses];
+  std::vector<KvItem> split_items[kNumSplitClasses];
+  std::vector<int32_t> reduce_off[kNumSplitClasses];
+  std::vector<KvReduce> reduce_items[kNumSplitClasses];
+  int32_t max_slots[kNumSplitClasses] = {0, 0, 0, 0};   // most partial tiles any one scope needs
 };
 
 struct DeviceLists {                            // device mirrors (pointers into one allocation)
   const QItem* q_items[kNumTileSizes];
   const KvItem* kv_items[kNumTileSizes];
   const Seg* segs;
+  const KvItem* split_items[kNumSplitClasses];
+  const KvReduce* reduce_items[kNumSplitClasses];
 };
 
 }  // namespace slimattn
@@ -86,7 +107,10 @@ int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const voi
                        const float* delta, void* dQ, const QItem* items, int n_items);
 int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                         int n_items, const Seg* segs, int load_acc, int store_final);
+                         int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
+// adds up the partial tiles of divided key tiles (in slot order) into dK/dV or the fp32 accumulators
+int launch_bwd_reduce_bf16(const LaunchCtx&, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
+                           const KvReduce* items, int n_items, int load_acc, int store_final);
 int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);
 
 // Tile sizes each kernel family uses (must be one of kTileSizes).

@@ -39,6 +39,72 @@ std::vector<Run> merge_runs(const slimattn_slice* sl, const int32_t* ids, int32_
   return out;
 }
 
+// Divided variants of one scope's 128-row key tiles.  With h KV heads a launch has items x h
+// blocks on kBlockSlots resident slots, so a tile whose query rows exceed a fraction of the
+// per-slot share W * h / kBlockSlots is cut into parts of about half a share (parts no shorter
+// than kMinPartRows).  A part is an item of
+// its own, with its own (cut) runs appended to segs and a partial-tile slot; slots of one tile are
+// consecutive and the reduction adds them in that order, so results do not depend on scheduling.
+constexpr int kBlockSlots = 512;          // 256 compute units x 2 resident blocks
+constexpr int64_t kMinPartRows = 1024;
+
+void append_split(ScopeLists& L, const std::vector<KvItem>& ki, const std::vector<int64_t>& weight) {
+  int64_t total = 0;
+  for (int64_t w : weight) total += w;
+  for (int c = 0; c < kNumSplitClasses; ++c) {
+    const int64_t heads = int64_t(1) << c;
+    // A tile is divided when it exceeds three quarters of the per-slot share (below that, the
+    // heavy-first dispatch already hides it), into parts of about half a share: the divided tiles
+    // then no longer decide the makespan.
+    const int64_t share = total * heads / kBlockSlots;
+    const int64_t target = std::max(kMinPartRows, (share / 2 + 127) / 128 * 128);
+    std::vector<KvItem> items;
+    std::vector<int64_t> w;
+    int32_t slots = 0;
+    for (size_t x = 0; x < ki.size(); ++x) {
+      const int64_t parts = std::min<int64_t>((weight[x] + target - 1) / target, weight[x] / kMinPartRows);
+      if (parts < 2 || 4 * weight[x] <= 3 * share) {
+        items.push_back(ki[x]);
+        w.push_back(weight[x]);
+        continue;
+      }
+      const int64_t chunk = ((weight[x] + parts - 1) / parts + 127) / 128 * 128;
+      L.reduce_items[c].push_back(KvReduce{ki[x].kv_row0, ki[x].kv_rows, slots, 0});
+      KvReduce& red = L.reduce_items[c].back();
+      // walk the tile's runs, closing a part whenever it holds `chunk` rows
+      int64_t have = 0;
+      int32_t part_seg_begin = (int32_t)L.segs.size();
+      auto close_part = [&]() {
+        items.push_back(KvItem{ki[x].kv_row0, ki[x].kv_rows, part_seg_begin, (int32_t)L.segs.size(), slots, 0, 0, 0});
+        w.push_back(have);
+        ++slots;
+        ++red.n_parts;
+        have = 0;
+        part_seg_begin = (int32_t)L.segs.size();
+      };
+      for (int32_t sgi = ki[x].seg_begin; sgi < ki[x].seg_end; ++sgi) {
+        const Seg sg = L.segs[sgi];
+        int32_t a = std::max(sg.q_lo, ki[x].kv_row0);
+        while (a < sg.q_hi) {
+          const int32_t take = (int32_t)std::min<int64_t>(sg.q_hi - a, chunk - have);
+          L.segs.push_back(Seg{a, a + take});
+          have += take;
+          a += take;
+          if (have == chunk) close_part();
+        }
+      }
+      if (have > 0) close_part();
+    }
+    std::vector<int32_t> order(items.size());
+    for (size_t x = 0; x < order.size(); ++x) order[x] = (int32_t)x;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return w[a] > w[b]; });
+    for (int32_t x : order) L.split_items[c].push_back(items[x]);
+    L.split_off[c].push_back((int32_t)L.split_items[c].size());
+    L.reduce_off[c].push_back((int32_t)L.reduce_items[c].size());
+    L.max_slots[c] = std::max(L.max_slots[c], slots);
+  }
+}
+
 void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
   const int32_t seg_base = (int32_t)L.segs.size();
   for (const Run& r : runs) L.segs.push_back(Seg{r.q_lo, r.q_hi});
@@ -66,7 +132,7 @@ void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
         while (runs[first].q_hi <= a) ++first;             // exists: the last run ends after a
         int64_t rows = 0;
         for (size_t r = first; r < j; ++r) rows += runs[r].q_hi - std::max(runs[r].q_lo, a);
-        ki.push_back(KvItem{a, std::min(B, kv_end - a), seg_base + (int32_t)first, seg_base + (int32_t)j});
+        ki.push_back(KvItem{a, std::min(B, kv_end - a), seg_base + (int32_t)first, seg_base + (int32_t)j, -1, 0, 0, 0});
         weight.push_back(rows);
       }
       i = j;
@@ -76,6 +142,7 @@ void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return weight[a] > weight[b]; });
     for (int32_t x : order) L.kv_items[z].push_back(ki[x]);
     L.kv_off[z].push_back((int32_t)L.kv_items[z].size());
+    if (B == kSplitTileRows) append_split(L, ki, weight);
   }
 }
 
@@ -127,6 +194,7 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     t->unit_slices[1].assign(bwd_unit_slices, bwd_unit_slices + n_slices);
     for (int pass = 0; pass < 2; ++pass) {
       for (int z = 0; z < kNumTileSizes; ++z) { t->per_unit[pass].q_off[z].push_back(0); t->per_unit[pass].kv_off[z].push_back(0); }
+      for (int c = 0; c < kNumSplitClasses; ++c) { t->per_unit[pass].split_off[c].push_back(0); t->per_unit[pass].reduce_off[c].push_back(0); }
       for (int32_t u = 0; u < t->n_units[pass]; ++u) {
         const int32_t a = t->unit_ptr[pass][u], b = t->unit_ptr[pass][u + 1];
         append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a));
@@ -135,12 +203,13 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     std::vector<int32_t> all(n_slices);
     for (int32_t i = 0; i < n_slices; ++i) all[i] = i;
     for (int z = 0; z < kNumTileSizes; ++z) { t->fused.q_off[z].push_back(0); t->fused.kv_off[z].push_back(0); }
+    for (int c = 0; c < kNumSplitClasses; ++c) { t->fused.split_off[c].push_back(0); t->fused.reduce_off[c].push_back(0); }
     append_scope(t->fused, merge_runs(slices, all.data(), n_slices));
 
     // one blob, one upload
     std::vector<char> blob;
     const size_t off_cu = place(blob, t->cu), off_sl = place(blob, t->slices);
-    size_t off_q[3][kNumTileSizes], off_kv[3][kNumTileSizes], off_seg[3];
+    size_t off_q[3][kNumTileSizes], off_kv[3][kNumTileSizes], off_seg[3], off_sp[3][kNumSplitClasses], off_rd[3][kNumSplitClasses];
     ScopeLists* lists[3] = {&t->per_unit[0], &t->per_unit[1], &t->fused};
     for (int s = 0; s < 3; ++s) {
       for (int z = 0; z < kNumTileSizes; ++z) {
@@ -148,6 +217,10 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
         off_kv[s][z] = place(blob, lists[s]->kv_items[z]);
       }
       off_seg[s] = place(blob, lists[s]->segs);
+      for (int c = 0; c < kNumSplitClasses; ++c) {
+        off_sp[s][c] = place(blob, lists[s]->split_items[c]);
+        off_rd[s][c] = place(blob, lists[s]->reduce_items[c]);
+      }
     }
     blob.resize(align_up(blob.size()) + 256);
     hipError_t e = hipGetDevice(&t->device);
@@ -169,6 +242,10 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
         dl[s]->kv_items[z] = (const KvItem*)(base + off_kv[s][z]);
       }
       dl[s]->segs = (const Seg*)(base + off_seg[s]);
+      for (int c = 0; c < kNumSplitClasses; ++c) {
+        dl[s]->split_items[c] = (const KvItem*)(base + off_sp[s][c]);
+        dl[s]->reduce_items[c] = (const KvReduce*)(base + off_rd[s][c]);
+      }
     }
   } catch (const std::bad_alloc&) {
     delete t;
@@ -192,6 +269,7 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
     case 2: return t->n_slices;
     case 3: return t->n_units[0];
     case 4: return t->n_units[1];
+    case 5: case 6: case 7: case 8: return (int64_t)t->fused.reduce_items[what - 5].size();
     default: return -1;
   }
 }
@@ -199,7 +277,10 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_t hkv, int32_t d) {
   if (!t || hq < 1 || hkv < 1 || d < 1) return 0;
   const size_t T = (size_t)t->total_tokens;
-  return align_up(2 * T * hkv * d * sizeof(float)) + 2 * align_up(T * hq * sizeof(float)) + 256;
+  const int c = split_class(hkv);
+  const size_t slots = (size_t)std::max({t->per_unit[0].max_slots[c], t->per_unit[1].max_slots[c], t->fused.max_slots[c]});
+  const size_t parts = slots * hkv * 2 * kSplitTileRows * d * sizeof(float);
+  return align_up(2 * T * hkv * d * sizeof(float)) + 2 * align_up(T * hq * sizeof(float)) + align_up(parts) + 256;
 }
 
 }  // extern "C"

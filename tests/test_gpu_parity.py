@@ -145,6 +145,31 @@ def test_bitwise_repeatable_and_grouping_invariant():
         assert float(np.max(np.abs(x - y))) <= TOL_G
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(4, 1, 64), (4, 2, 128)])
+def test_bf16_divided_key_tiles(hq, hkv, d):
+    # One sample long enough that the dK/dV work of its first key tiles is divided among several
+    # blocks (partial fp32 tiles + a reduction in fixed order), in the whole-list scope and, with two
+    # backward units of interleaved slices, inside the per-unit scopes, where the cuts fall inside
+    # runs of query rows.  Same oracle, same tolerances, and bitwise repeatable.
+    L = [4500, 300, 64]
+    cu, sl, fu, bu = _tables(L, 512, ("PER_SAMPLE", {}), ("ROUND_ROBIN", {"m": 2, "descending": True}))
+    q, k, v, dO = _draw(sum(L), hq, hkv, d, 23, True, 0.5, 0.1)
+    scale = d ** -0.5
+    ref = _oracle(q, k, v, dO, cu, scale)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    cls = {1: 0, 2: 1}[hkv]
+    assert prob.tables.count(5 + cls) > 0, "no key tile was divided: the case does not cover the reduction path"
+    _run_modes(prob, ref, TOL_O, TOL_G, f"divided {hq}/{hkv}/{d}")
+    runs = []
+    for flags in (0, 0, S.FLAG_PER_UNIT_LAUNCH, S.FLAG_PER_UNIT_LAUNCH):
+        _poison(prob)
+        prob.forward(flags=flags); prob.backward(flags=flags); torch.cuda.synchronize()
+        runs.append([t.view(torch.int16).cpu().numpy().copy() for t in (prob.dK, prob.dV)])
+    for a, b in ((runs[0], runs[1]), (runs[2], runs[3])):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y), "dK/dV differ between two identical runs"
+
+
 def test_cfg1_full_size_sampled_rows_and_identities():
     w = W.WORKLOADS["cfg1_llama8b_32k"]
     rng = np.random.default_rng(1)
