@@ -76,6 +76,9 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
           if (i & 1) dpc = mfma32(f, dof[i >> 1], dpc);
           else sc = mfma32(f, qf[i >> 1], sc);
         });
+    // the element-wise part runs at raised priority: a wave that streams products would otherwise
+    // keep the vector issue port and starve the other wave's softmax
+    __builtin_amdgcn_s_setprio(3);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float p = __builtin_amdgcn_exp2f(sc[r]);
@@ -84,6 +87,7 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
     }
     dsf[2 * b] = pack8(sc, 0);
     dsf[2 * b + 1] = pack8(sc, 8);
+    __builtin_amdgcn_s_setprio(0);
   }
   // dQ^T += K^T dS^T: one batch of four K^T fragments (the four 16-key steps) per head-dim block
   Tr4 tb[NDB];

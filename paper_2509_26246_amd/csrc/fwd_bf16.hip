@@ -447,7 +447,10 @@ __global__ __launch_bounds__(512, 2) void fwd_pair_bf16_kernel(const bf16* __res
     stage_tile<D, kFwdBK, 512>(lds + (PAR) * kBufBytes, srcK, (j + 2) * kFwdBK, tid);                              \
     stage_tile<D, kFwdBK, 512>(lds + (1 - (PAR)) * kBufBytes + kTileBytes, srcV, (j + 1) * kFwdBK, tid);           \
     fwd_products<D, true, true, (1 - (PAR)) * kBufBytes, (PAR) * kBufBytes>(pk, pv, qf, sacc, pf, oacc, m_ref, handoff); \
+    /* a wave streaming products would otherwise keep the vector issue port to itself */                        \
+    __builtin_amdgcn_s_setprio(3);                                                                                 \
     fwd_softmax<D>(sacc, pf, oacc, m_ref, l_run, rel0 - (j + 1) * kFwdBK, j + 1 >= n_full);                        \
+    __builtin_amdgcn_s_setprio(0);                                                                                 \
     __builtin_amdgcn_s_waitcnt(0x0f70); /* vmcnt(0) */                                                             \
     __builtin_amdgcn_s_barrier();                                                                                  \
   }
