@@ -223,19 +223,25 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
 // groups work on the same 128 query rows and the same K/V tiles (staged once for both) but on two
 // different query heads of the KV group.  A wave's tile work is split into a product phase
 // M(j) = { S^T(j+1) = K(j+1) Q^T ; O^T += V(j)^T P(j)^T } (matrix cores + LDS reads only) and a
-// softmax phase X(j+1) (vector ALU only), and the groups run them in opposite slots, separated by
-// block barriers: while one group's products occupy the matrix cores and the LDS, the other
-// group's softmax runs on the vector ALUs of the same SIMDs.
+// softmax phase X(j+1) (vector ALU only), and the groups run them in opposite slots: while one
+// group's products occupy the matrix cores and the LDS, the other group's softmax runs on the
+// vector ALUs of the same SIMDs (at raised wave priority: a wave that streams products would
+// otherwise keep the vector issue port to itself).
 //
 //   slot      0          1      2      3      4
 //   group 0   S(0) X(0)  M(0)   X(1)   M(1)   X(2) ...
 //   group 1   S(0)       X(0)   M(0)   X(1)   M(1) ...
 //
+// Two block barriers per tile keep the groups in step.  One closes a group's softmax phase; the
+// other sits inside the product phase, two operand batches before its end, after a wait for all of
+// the wave's LDS reads: the other group then starts fetching its first operands while this wave's
+// last products drain, and every read of the phase is known to be complete at the barrier.
 // K(j+2) and V(j+1) are loaded into the buffers of K(j) and V(j-1) by every wave at the start of
-// its M(j); the last reader of those buffers is group 1's M(j-1), one slot before group 0's M(j).
+// its M(j); those buffers were last read in the other group's M(j-1), behind that barrier.
 
-// Products of one phase for this wave.  All operand fragments come through asm batches of four
-// LDS reads (row reads for K, transpose reads for V), kDepth batches ahead of their use.
+// Products of one phase for this wave.  All operand fragments come through asm batches of LDS
+// reads (row reads for K, transpose reads for V), kDepth batches ahead of their use; KOFF / VOFF
+// select the K and V buffers (byte offsets folded into the instructions' immediates).
 struct NoHandoff { __device__ __forceinline__ void operator()() const {} };
 
 // `handoff()` runs when only kTail batches are left, all of them already issued: the caller waits
@@ -252,10 +258,7 @@ __device__ __forceinline__ void fwd_products(const lds_cptr (&pk)[D / 16], const
   // accumulators, so a wave that has the matrix core to itself does not wait on its own previous
   // product.
   constexpr int NSU = DO_S ? NKS : 0, NPU = DO_PV ? 2 * NDB : 0, NU = NSU + NPU;
-#ifndef SLIMATTN_FWD_DEPTH
-#define SLIMATTN_FWD_DEPTH 3
-#endif
-  constexpr int kDepth = SLIMATTN_FWD_DEPTH, kTail = 2, kKb = 32 * kRowBytes;
+  constexpr int kDepth = 3, kTail = 2, kKb = 32 * kRowBytes;
   static_assert(kTail < kDepth, "the tail batches must have been issued before the handoff");
   R2 ru[NSU ? NSU : 1];
   Tr2 tu[NPU ? NPU : 1];
@@ -384,18 +387,20 @@ __global__ __launch_bounds__(512, 2) void fwd_pair_bf16_kernel(const bf16* __res
   const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
   // tiles this wave sees without a mask (a prefix of the tile sequence)
   const int n_full = max(0, (q0w - it.kv_start + 1) / kFwdBK);
+  // The block's global loads are all issued before anything waits: the Q rows first, then the first
+  // tiles.  One memory latency is then paid once per block.
+  bf16x8 qf[NKS];
+  {
+    const bf16* qp = q + ((size_t)min(my_row, T - 1) * Hq + h) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  }
   const TileSource srcK = make_tile_source<D, 512>(k, it.kv_start, Hkv, hk, T, tid);
   const TileSource srcV = make_tile_source<D, 512>(v, it.kv_start, Hkv, hk, T, tid);
   stage_tile<D, kFwdBK, 512>(lds, srcK, 0, tid);
   stage_tile<D, kFwdBK, 512>(lds + kTileBytes, srcV, 0, tid);
   stage_tile<D, kFwdBK, 512>(lds + kBufBytes, srcK, kFwdBK, tid);
 
-  bf16x8 qf[NKS];
-  {
-    const bf16* qp = q + ((size_t)min(my_row, T - 1) * Hq + h) * D + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = scale8(*reinterpret_cast<const bf16x8*>(qp + 16 * ks), scale * kLog2e);
-  }
   lds_cptr pk[NKS], pv[NDB][2];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) pk[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
@@ -408,18 +413,10 @@ __global__ __launch_bounds__(512, 2) void fwd_pair_bf16_kernel(const bf16* __res
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_ref = 0.f, l_run = 0.f;
-  {
-    const bf16* kp = k + ((size_t)it.kv_start * Hkv + hk) * D + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) m_ref = fmaf((float)qf[ks][e], (float)k0[e], m_ref);
-    }
-    m_ref += xor32(m_ref);
-  }
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) qf[ks] = scale8(qf[ks], scale * kLog2e);
 
   const int rel0 = my_row - it.kv_start - 4 * half;      // rel of tile t = rel0 - t * kFwdBK
   // A tile beyond the wave's last visible one is treated as fully masked (its probabilities are
@@ -427,6 +424,15 @@ __global__ __launch_bounds__(512, 2) void fwd_pair_bf16_kernel(const bf16* __res
   // otherwise wait at the barriers for the block's lower rows.
   // slot 0: S(0) for both groups, X(0) for group 0 only
   fwd_products<D, true, false, 0, 0>(pk, pv, qf, sacc, pf, oacc, m_ref);
+  {
+    // Reference maximum (log2 units): the row's score against the first key of the sample, which
+    // every row sees.  It is element [key 0][row] of S^T(0): register 0 of the lower half-wave.
+    m_ref = __shfl(sacc[0][0], l32);                // both halves take the lower half's value
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[b][r] -= m_ref;
+  }
   if (grp) __syncthreads();
   fwd_softmax<D>(sacc, pf, oacc, m_ref, l_run, rel0, n_full < 1);
   __syncthreads();
