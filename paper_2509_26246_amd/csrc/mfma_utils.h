@@ -41,30 +41,6 @@ __device__ __forceinline__ int lds_off16<64>(int row, int unit) {
   return R * 256 + ((u ^ f) << 4);
 }
 
-// Row-major fragment: 8 consecutive columns (col0 multiple of 8) of one row.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_frag_row(const char* tile, int row, int col0) {
-  return *reinterpret_cast<const bf16x8*>(tile + lds_off16<D>(row, col0 >> 3));
-}
-
-// Transposed fragment for an A operand with m = column, k = row: lane l receives, for column
-// col0 + (l % 32), the rows {row0 + 4*half + 0..3} and {row0 + 8 + 4*half + 0..3}.
-// Built from two LDS transpose loads; in each, the 16 lanes of a group supply the addresses of
-// 4 rows x 4 chunks of 4 columns, and lane i gets column i of the four rows.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int row0, int col0, int lane) {
-  const int i = lane & 15, grp = lane >> 4;
-  const int row = row0 + 4 * (grp >> 1) + (i >> 2);
-  const int col = col0 + 16 * (grp & 1) + 4 * (i & 3);
-  const int off = lds_off16<D>(row, col >> 3) + ((col & 4) << 1);
-  const int off2 = lds_off16<D>(row + 8, col >> 3) + ((col & 4) << 1);
-  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(tile + off));
-  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(tile + off2));
-  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
-  short8v r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
-}
-
 // Pack eight fp32 accumulators (registers r0 .. r0+7 of a C tile) into a bf16 B operand
 // (four packed round-to-nearest-even conversions).
 typedef __attribute__((__vector_size__(8 * sizeof(float)))) float floatx8;
@@ -95,8 +71,6 @@ __device__ __forceinline__ float sum8(bf16x8 a, float acc) {
   }
   return acc;
 }
-
-struct FragPair { bf16x8 a, b; };
 
 // Software-pipelined operand stream: N fragments, each read from LDS kPre steps before the
 // product that consumes it.  `load(i)` returns fragment i, `use(i, frag)` issues its products.
@@ -133,8 +107,12 @@ template <int D>
 __device__ __forceinline__ lds_cptr lds_row_ptr(lds_cptr tile, int row, int col0) {
   return keep(tile + lds_off16<D>(row, col0 >> 3));
 }
-// Pointers for lds_frag_tr at row0 = 0: p0 serves rows {4*half + 0..3}, p1 rows {8 + 4*half + 0..3};
-// a fragment at row0 = 16*s is read at both pointers + 16*s*(2*D) bytes.
+// Transposed fragment for an A operand with m = column, k = row: lane l receives, for column
+// col0 + (l % 32), the rows {row0 + 4*half + 0..3} and {row0 + 8 + 4*half + 0..3}.  It is built
+// from two LDS transpose loads; in each, the 16 lanes of a group supply the addresses of 4 rows x
+// 4 chunks of 4 columns, and lane i gets column i of the four rows.  These are the two addresses
+// for row0 = 0: p0 serves rows {4*half + 0..3}, p1 rows {8 + 4*half + 0..3}; a fragment at
+// row0 = 16*s is read at both pointers + 16*s*(2*D) bytes.
 template <int D>
 __device__ __forceinline__ void lds_tr_ptrs(lds_cptr tile, int col0, int lane, lds_cptr& p0, lds_cptr& p1) {
   const int i = lane & 15, grp = lane >> 4;
@@ -146,14 +124,6 @@ __device__ __forceinline__ void lds_tr_ptrs(lds_cptr tile, int col0, int lane, l
 __device__ __forceinline__ bf16x8 lds_ld_row(lds_cptr p, int byte_off) {
   return *reinterpret_cast<LDS_PTR(const bf16x8)>(p + byte_off);
 }
-__device__ __forceinline__ bf16x8 lds_ld_tr(lds_cptr p0, lds_cptr p1, int byte_off) {
-  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(p0 + byte_off));
-  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(p1 + byte_off));
-  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
-  short8v r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
-}
-
 // ---- transposed fragment stream through inline asm ---------------------------------------------
 // The compiler's wait-count insertion treats an LDS transpose load as possibly reading what an
 // outstanding direct global->LDS load is still writing and puts a full vmcnt(0) wait in front of
@@ -244,33 +214,7 @@ __device__ __forceinline__ void tr2_wait(Tr2& p) {
 }
 
 // Row-fragment batches through inline asm (same reason and same protocol as the transposed ones):
-// four 16-byte fragment loads per batch, each with its own address register and byte offset.
-struct R4 { bf16x8 f[4]; };
-#define SLIMATTN_R4_READS                               \
-  "ds_read_b128 %0, %[a0] offset:%[o0]\n\t"             \
-  "ds_read_b128 %1, %[a1] offset:%[o1]\n\t"             \
-  "ds_read_b128 %2, %[a2] offset:%[o2]\n\t"             \
-  "ds_read_b128 %3, %[a3] offset:%[o3]\n\t"
-template <int O0, int O1, int O2, int O3>
-__device__ __forceinline__ void r4_issue(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n) {
-  asm volatile(SLIMATTN_R4_READS
-               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3])
-               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
-                 [o3] "n"(O3));
-}
-template <int O0, int O1, int O2, int O3>
-__device__ __forceinline__ void r4_issue_wait(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n, R4& p) {
-  asm volatile(SLIMATTN_R4_READS "s_waitcnt lgkmcnt(4)"
-               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3]), "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]),
-                 "+v"(p.f[3])
-               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
-                 [o3] "n"(O3));
-}
-__device__ __forceinline__ void r4_wait(R4& p) {
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]), "+v"(p.f[3]));
-}
-
-// Two-fragment row batches for kernels that are short of registers.
+// two 16-byte fragment loads per batch, each with its own address register and byte offset.
 struct R2 { bf16x8 f[2]; };
 template <int O0, int O1>
 __device__ __forceinline__ void r2_issue(lds_cptr a0, lds_cptr a1, R2& n) {
@@ -288,10 +232,6 @@ __device__ __forceinline__ void r2_wait(R2& p) { asm volatile("s_waitcnt lgkmcnt
 
 // Wait until at most N LDS operations issued by this wave are outstanding; `p` (a batch issued
 // before those N) is then complete, and its consumers are ordered after the wait.
-template <int N>
-__device__ __forceinline__ void lds_wait(R4& p) {
-  asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]), "+v"(p.f[3]) : [n] "n"(N));
-}
 template <int N>
 __device__ __forceinline__ void lds_wait(R2& p) {
   asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]) : [n] "n"(N));
