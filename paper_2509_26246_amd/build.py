@@ -9,7 +9,10 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslimattn.so")
-SOURCES = ["builder.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "bwd_bf16.hip"]
+SOURCES = ["builder.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "dkdv128_bf16.hip"]
+# dkdv128_bf16.hip keeps its dK/dV accumulators in the accumulation registers through inline asm; the
+# builtin products of the same kernel must then be told to stay in architectural registers.
+EXTRA_FLAGS = {"dkdv128_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -23,7 +26,7 @@ def _hipcc() -> str:
 
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA_FLAGS.get(src, []), "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr[-4000:]}")
@@ -33,7 +36,7 @@ def _compile(src: str, objdir: str) -> str:
 def build(verbose: bool = False) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(lambda s: _compile(s, objdir), SOURCES))
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -139,20 +139,25 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
       return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
                                        delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
                                        store_final)
-                 : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
-                                        store_final, parts);
+                 : use_dkdv128(p->dtype, p->head_dim)
+                     ? launch_bwd_dkdv128_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                                               store_final, parts)
+                     : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                                            store_final, parts);
     });
   };
   // bf16: the key-tile list in which heavy tiles are divided among several blocks, followed by the
   // launch that adds the parts up (a scope without divided tiles has an empty reduction list)
   auto run_dkdv_split = [&](const ScopeLists& L, const DeviceLists& D, int u, int load_acc, int store_final) -> int {
-    const int a = L.split_off[sc][u], b = L.split_off[sc][u + 1];
-    int e = run_dkdv(D.split_items[sc] + a, b - a, D.segs, load_acc, store_final);
+    const int tile_rows = dkdv_kv_tile(p->dtype, p->head_dim), ti = split_tile_index(tile_rows);
+    const int a = L.split_off[ti][sc][u], b = L.split_off[ti][sc][u + 1];
+    int e = run_dkdv(D.split_items[ti][sc] + a, b - a, D.segs, load_acc, store_final);
     if (e != 0) return e;
-    const int ra = L.reduce_off[sc][u], rb = L.reduce_off[sc][u + 1];
+    const int ra = L.reduce_off[ti][sc][u], rb = L.reduce_off[ti][sc][u + 1];
     if (rb == ra) return 0;
     return timed(SLIMATTN_K_FINALIZE, stream, [&] {
-      return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[sc] + ra, rb - ra, load_acc, store_final);
+      return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[ti][sc] + ra, rb - ra, load_acc,
+                                    store_final, tile_rows);
     });
   };
 

@@ -22,7 +22,7 @@ namespace {
 
 constexpr int kDqBQ = 128, kDqBK = 64;
 constexpr int kKvOwn = 128;
-static_assert(kKvOwn == kSplitTileRows, "divided key-tile lists are built for this tile");
+static_assert(kKvOwn == kSplitTileRows[0], "divided key-tile lists are built for this tile");
 // query rows per step of the dK/dV walk: at head_dim 128 the wave's V fragments live in LDS and the
 // step is 32 rows, which keeps the kernel at two waves per SIMD without register spills
 template <int D> struct DkdvCfg { static constexpr int kQStep = D == 128 ? 32 : 64; static constexpr bool kVInLds = D == 128; };
@@ -472,10 +472,10 @@ template <int D>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ parts, float* __restrict__ acc_dk,
                                                            float* __restrict__ acc_dv, bf16* __restrict__ dK,
                                                            bf16* __restrict__ dV, const KvReduce* __restrict__ items,
-                                                           int Hkv, int load_acc, int store_final) {
+                                                           int Hkv, int load_acc, int store_final, int tile_rows) {
   const KvReduce it = items[blockIdx.x / Hkv];
   const int hk = blockIdx.x % Hkv;
-  constexpr int kTile = kKvOwn * D;
+  const int kTile = tile_rows * D;                     // elements of one partial dK (or dV) tile
   for (int e = threadIdx.x * 4; e < 2 * kTile; e += 256 * 4) {
     const int which = e / kTile, r = (e % kTile) / D, c = e % D;
     if (r >= it.kv_rows) continue;
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 }  // namespace
 
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
-int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kKvOwn; }
+int dkdv_kv_tile(int dtype, int head_dim) { return dtype == SLIMATTN_F32 ? 64 : use_dkdv128(dtype, head_dim) ? 256 : kKvOwn; }
 
 int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2) {
   const slimattn_params& p = *c.p;
@@ -560,16 +560,16 @@ int launch_bwd_dkdv_bf16(const LaunchCtx& c, const void* q, const void* k, const
 }
 
 int launch_bwd_reduce_bf16(const LaunchCtx& c, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
-                           const KvReduce* items, int n_items, int load_acc, int store_final) {
+                           const KvReduce* items, int n_items, int load_acc, int store_final, int tile_rows) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(reduce_parts_kernel<128>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
-                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final);
+                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final, tile_rows);
   else
     hipLaunchKernelGGL(reduce_parts_kernel<64>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
-                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final);
+                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final, tile_rows);
   return (int)hipGetLastError();
 }
 

@@ -1,0 +1,491 @@
+// dK/dV at head_dim 128, bf16 inputs: one wave per SIMD, 64 key rows per wave.
+//
+// What it computes is the dK/dV step of the backward (see bwd_bf16.hip): a block owns key rows of one
+// KV head and walks every query row of the launch scope at or after them, for every query head of the
+// group, in a fixed order; S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.
+//
+// Shape on CDNA4.  The kernel that keeps two waves per SIMD (32 keys per wave) is at its register
+// limit and reads 1.25 KB of LDS per product.  Here a block is 4 waves, one per SIMD, and a wave owns
+// 64 keys (two 32-key blocks): every Q, dO, Q^T and dO^T fragment read from LDS feeds two products, the
+// 256 accumulator registers of dK^T and dV^T live in the accumulation half of the register file
+// (they are only ever touched by products, issued from inline asm with an "a" constraint: the compiler
+// cannot be told to keep a builtin product's accumulator there), and everything a vector instruction
+// reads stays in the 256 architectural registers.  With no second wave on the SIMD, the wave overlaps
+// its own work: an iteration runs the score products of step t+1 (S, dP: 32 products, LDS row reads),
+// then the 32 gradient products of step t with the element-wise work of step t+1 (exp2, dS, packing)
+// spread between them, one value after each product.  Query steps are 32 rows; their Q/dO tiles are
+// staged two steps ahead through three LDS stages; the block's 256 V rows stay in LDS.
+//
+// Hazards of the inline-asm products: their results are read only by later products on the same
+// accumulator (at least three other products in between) and, after the loop, behind explicit
+// wait states; their B operands were packed by vector instructions a whole phase earlier.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "mfma_utils.h"
+
+namespace slimattn {
+namespace {
+
+constexpr int kD = 128, kNKS = kD / 16, kNDB = kD / 32, kRowBytes = kD * 2;
+constexpr int kKeys = 256;                              // key rows per block: 4 waves x 64
+constexpr int kQStep = 32;
+constexpr int kTileBytes = kQStep * kRowBytes;          // one Q or dO tile
+constexpr int kStageBytes = 2 * kTileBytes;             // [Q tile, dO tile]
+constexpr int kStages = 3;
+constexpr int kVBase = kStages * kStageBytes;
+constexpr int kVBytes = kKeys * kRowBytes;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uintx4;   // a packed bf16x8 fragment, by dword
+__device__ __forceinline__ bf16x8 as_frag(uintx4 x) { return __builtin_bit_cast(bf16x8, x); }
+
+// START: the product starts its accumulator (C = 0) instead of adding to it.  The accumulators are never
+// initialised by compiler-generated moves, and a START product waits a few cycles before it issues: the
+// compiler does not know that the asm is a matrix product, so it separates neither such a move nor a
+// vector write of an operand register (the zero fragments of the first step are written right in front
+// of the first product) from it by the wait states the hardware needs.  The other products read only
+// registers written a whole phase earlier (packed P, dS) or by waited-for LDS reads.
+template <bool START>
+__device__ __forceinline__ void mfma_acc(floatx16& acc, bf16x8 a, bf16x8 b) {
+  if (START) asm volatile("s_nop 7\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(acc) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Score products of one step: s[kb] = Q K_kb^T - lse (log2 units, kf holds k * scale * log2 e),
+// dp[kb] = dO V_kb^T - delta, for the wave's two key blocks.  pq[] point at the step's Q tile (the dO
+// tile follows it), v_rel is the byte distance from there to this wave's V rows.  The accumulators
+// start at minus the row statistics (local row of register r: 8 (r/4) + 4 half + r%4); where the row
+// lies before the lane's key or at/after the end of the query run (local rows outside
+// [rel_lo[kb], rel_hi), `masked` steps only) the score starts at -inf, so that its probability and
+// its dS come out as zero.  One batch of LDS reads per head-dim step: the Q and dO fragments and the two
+// V fragments.
+template <class Between>
+__device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v_rel, LDS_PTR(const float) s_lse, LDS_PTR(const float) s_delta,
+                                               const bf16x8 (&kf)[2][kNKS], floatx16 (&s)[2], floatx16 (&dp)[2], int half,
+                                               bool masked, const int (&rel_lo)[2], int rel_hi, Between&& between) {
+  // the statistics are stored negated; every accumulator quad gets an LDS read of its own (volatile:
+  // a shared read plus register copies would cost vector instructions that nothing overlaps)
+#pragma unroll
+  for (int gq = 0; gq < 4; ++gq) {
+    LDS_PTR(const volatile floatx4) pl = (LDS_PTR(const volatile floatx4))(s_lse + 8 * gq + 4 * half);
+    LDS_PTR(const volatile floatx4) pd = (LDS_PTR(const volatile floatx4))(s_delta + 8 * gq + 4 * half);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const floatx4 l4 = *pl, d4 = *pd;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        s[kb][4 * gq + x] = l4[x];
+        dp[kb][4 * gq + x] = d4[x];
+      }
+    }
+  }
+  if (masked) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const unsigned span = (unsigned)max(rel_hi - rel_lo[kb], 0);   // c - rel_lo in [0, span) <=> the pair counts
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int c = 8 * (r >> 2) + (r & 3);           // c + 4*half = local row
+        s[kb][r] = (unsigned)(c - rel_lo[kb]) < span ? s[kb][r] : -INFINITY;
+      }
+    }
+  }
+#ifdef DK128_TIMING
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(s[0]), "+v"(s[1]), "+v"(dp[0]), "+v"(dp[1]));
+  between(IC<100>{});
+#endif
+  // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
+  // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
+  // issue time of a plain instruction: four in a row would outlast the product they follow).
+  R4 g[kNKS];
+  lds_cptr pv = pq[0];
+  auto issue_one = [&](auto uc, auto ic) {
+    constexpr int u = decltype(uc)::value, i = decltype(ic)::value;
+    if constexpr (i == 0) r1_issue<0>(pq[u], g[u].f[0]);
+    if constexpr (i == 1) { r1_issue<kTileBytes>(pq[u], g[u].f[1]); pv = pq[u] + v_rel; }
+    if constexpr (i == 2) r1_issue<0>(pv, g[u].f[2]);
+    if constexpr (i == 3) r1_issue<32 * kRowBytes>(pv, g[u].f[3]);
+  };
+  static_for<0, 2>([&](auto uc) { static_for<0, 4>([&](auto ic) { issue_one(uc, ic); }); });
+  static_for<0, kNKS>([&](auto uc) {
+    constexpr int u = decltype(uc)::value;
+    constexpr bool more = u + 2 < kNKS;
+    lds_wait<(u + 1 < kNKS) ? 4 : 0>(g[u]);
+    s[0] = mfma32(g[u].f[0], kf[0][u], s[0]);
+    if constexpr (more) issue_one(IC<u + 2>{}, IC<0>{});
+    between(IC<4 * u + 0>{});
+    __builtin_amdgcn_sched_barrier(0);
+    s[1] = mfma32(g[u].f[0], kf[1][u], s[1]);
+    if constexpr (more) issue_one(IC<u + 2>{}, IC<1>{});
+    between(IC<4 * u + 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    dp[0] = mfma32(g[u].f[1], g[u].f[2], dp[0]);
+    if constexpr (more) issue_one(IC<u + 2>{}, IC<2>{});
+    between(IC<4 * u + 2>{});
+    __builtin_amdgcn_sched_barrier(0);
+    dp[1] = mfma32(g[u].f[1], g[u].f[3], dp[1]);
+    if constexpr (more) issue_one(IC<u + 2>{}, IC<3>{});
+    between(IC<4 * u + 3>{});
+    __builtin_amdgcn_sched_barrier(0);
+  });
+}
+
+// Element-wise work, P = exp2(S - lse) and dS = P (dP - delta), as a stream of 32 values (value j:
+// key block j / 16, register j % 16) cut into slots, one slot behind each gradient product.  Slot j:
+// the exponential of value j, the dS product of value j - 1, and one packing to bf16: P of the pair
+// (j - 1, j) in odd slots, dS of the pair (j - 2, j - 1) in even ones; the last slot also finishes
+// value 31.  One transcendental and two plain vector instructions: with the product's own issue that
+// fills, and does not exceed, the time the matrix unit spends on one product.  Each slot is one asm
+// statement: the compiler keeps asm statements in program order (as ordinary code it moves the whole
+// stream behind the last product of the loop body, where nothing overlaps it) and puts no wait states
+// between the instructions.  A transcendental result may not be read by the very next vector
+// instruction: the instruction behind each exponential reads other registers.
+template <int J>
+__device__ __forceinline__ void ew_slot(floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2], uintx4 (&nds)[2][2]) {
+  constexpr int kb = J >> 4, r = J & 15;
+  constexpr int k1 = (J - 1) >> 4, r1 = (J - 1) & 15;   // value j - 1
+  constexpr int k2 = (J - 2) >> 4, r2 = (J - 2) & 15;   // value j - 2
+  float e = s[kb][r];
+  if constexpr (J == 0) {
+    asm volatile("v_exp_f32 %0, %0" : "+v"(e));
+    s[kb][r] = e;
+  } else if constexpr (J & 1) {
+    float m = dp[k1][r1];
+    unsigned w;
+    asm volatile("v_exp_f32 %0, %0\n\tv_mul_f32 %1, %3, %1\n\tv_cvt_pk_bf16_f32 %2, %3, %0"
+                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[k1][r1]));
+    s[kb][r] = e;
+    dp[k1][r1] = m;
+    npf[kb][r >> 3][(r & 7) >> 1] = w;
+    if constexpr (J == 31) {
+      float m2 = dp[1][15];
+      unsigned w2;
+      asm volatile("v_mul_f32 %0, %2, %0\n\tv_cvt_pk_bf16_f32 %1, %3, %0" : "+v"(m2), "=&v"(w2) : "v"(e), "v"(dp[1][14]));
+      dp[1][15] = m2;
+      nds[1][1][3] = w2;
+    }
+  } else {
+    float m = dp[k1][r1];
+    unsigned w;
+    asm volatile("v_exp_f32 %0, %0\n\tv_mul_f32 %1, %3, %1\n\tv_cvt_pk_bf16_f32 %2, %4, %1"
+                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[k1][r1]), "v"(dp[k2][r2]));
+    s[kb][r] = e;
+    dp[k1][r1] = m;
+    nds[k2][r2 >> 3][(r2 & 7) >> 1] = w;
+  }
+}
+
+// Gradient products of one step, dV_kb^T += dO^T P_kb and dK_kb^T += Q^T dS_kb, with P, dS packed in
+// pf[kb][half16], ds[kb][half16]; pqt[][] point at the step's Q tile.  Per head-dim block and 16-row half
+// one batch of two transposed fragments (dO^T, Q^T), each feeding both key blocks.  The element-wise work
+// of the next step (its scores in s, dp) is spread between the products, one value after each, and its
+// packed results are left in npf, nds.  FIRST: the block's first call, which starts the accumulators.
+template <bool FIRST>
+__device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB][2], const uintx4 (&pf)[2][2],
+                                                  const uintx4 (&ds)[2][2], floatx16 (&dk)[2][kNDB], floatx16 (&dv)[2][kNDB],
+                                                  floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2],
+                                                  uintx4 (&nds)[2][2]) {
+  constexpr int NB = 2 * kNDB;
+  Tr2 tb[NB];
+  auto issue = [&](auto ic) {
+    constexpr int b = decltype(ic)::value, st = b / kNDB, db = b % kNDB;
+    tr2_issue<st * 16 * kRowBytes + kTileBytes, st * 16 * kRowBytes>(pqt[db][0], pqt[db][1], tb[b]);
+  };
+  static_for<0, 2>(issue);
+  static_for<0, NB>([&](auto ic) {
+    constexpr int b = decltype(ic)::value, st = b / kNDB, db = b % kNDB;   // first 16-row half first: its P, dS die early
+    constexpr int behind = 4 * ((NB - 1 - b) < 2 ? (NB - 1 - b) : 2);
+    if constexpr (b + 2 < NB) issue(IC<b + 2>{});
+    lds_wait<behind>(tb[b]);
+    constexpr bool kStart = FIRST && st == 0;
+    mfma_acc<kStart>(dv[0][db], tr2_frag(tb[b], 0), as_frag(pf[0][st]));
+    ew_slot<4 * b + 0>(s, dp, npf, nds);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_acc<kStart>(dv[1][db], tr2_frag(tb[b], 0), as_frag(pf[1][st]));
+    ew_slot<4 * b + 1>(s, dp, npf, nds);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_acc<kStart>(dk[0][db], tr2_frag(tb[b], 1), as_frag(ds[0][st]));
+    ew_slot<4 * b + 2>(s, dp, npf, nds);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_acc<kStart>(dk[1][db], tr2_frag(tb[b], 1), as_frag(ds[1][st]));
+    ew_slot<4 * b + 3>(s, dp, npf, nds);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+}
+
+// p += d as an asm statement: stays in the slot where it is written (the compiler gathers plain
+// additions of this kind in one place, where they outlast the product they should hide behind).
+__device__ __forceinline__ void lds_ptr_add(lds_cptr& p, int d) {
+  unsigned x = (unsigned)(size_t)p;
+  asm volatile("v_add_u32 %0, %1, %0" : "+v"(x) : "s"(d));
+  p = (lds_cptr)(size_t)x;
+}
+
+struct Step { int i0, hi, head; };                      // rows [i0, min(i0 + 32, hi)) of one query head
+
+__global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
+    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
+    const float* __restrict__ lse2, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
+    bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
+    int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
+  __shared__ __attribute__((aligned(1024))) char smem[kVBase + kVBytes];   // three [Q, dO] stages, then the V tile
+  __shared__ __attribute__((aligned(16))) float s_stat[kStages][2][kQStep];  // [stage][lse2, delta][row]
+
+  const int g = Hq / Hkv;
+  const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
+  if (item_idx >= n_items) return;
+  const KvItem it = items[item_idx];
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int kv0w = it.kv_row0 + 64 * wave, kv_end = it.kv_row0 + it.kv_rows;
+  LDS_PTR(char) lds = (LDS_PTR(char))smem;
+
+  // Flattened walk (block-uniform): runs from the last to the first, inside a run steps of 32 rows from
+  // the top down, inside a step the heads of the group.
+  int sgi = it.seg_end - 1, hh = 0;
+  Seg sg = segs[sgi];
+  int lo = max(sg.q_lo, it.kv_row0);
+  int n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
+  bool more = true;                                     // the walk has a step that was not handed out yet
+  auto next_step = [&](Step& d) -> bool {
+    if (!more) return false;
+    d.i0 = lo + n * kQStep;
+    d.hi = sg.q_hi;
+    d.head = hk * g + hh;
+    if (++hh == g) {
+      hh = 0;
+      if (--n < 0) {
+        if (--sgi < it.seg_begin) {
+          more = false;
+        } else {
+          sg = segs[sgi];
+          lo = max(sg.q_lo, it.kv_row0);
+          n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
+        }
+      }
+    }
+    return true;
+  };
+
+  const TileSource srcQ = make_tile_source<kD, 256>(q, it.kv_row0, Hq, 0, T, tid);
+  const TileSource srcDO = make_tile_source<kD, 256>(dO, it.kv_row0, Hq, 0, T, tid);
+  float pre_stat = 0.f;                                 // a staged step's lse2 (threads 0..31) / delta (32..63)
+  auto stage = [&](const Step& d, int st) {             // statistics into a register, tiles straight into LDS
+    if (tid < 2 * kQStep) {
+      const int r = min(d.i0 + (tid & (kQStep - 1)), T - 1);
+      pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)d.head * T + r];
+    }
+    TileSource a = srcQ, b = srcDO;
+    a.voff += d.head * kRowBytes;
+    b.voff += d.head * kRowBytes;
+    stage_tile<kD, kQStep, 256>(lds + st * kStageBytes, a, d.i0 - it.kv_row0, tid);
+    stage_tile<kD, kQStep, 256>(lds + st * kStageBytes + kTileBytes, b, d.i0 - it.kv_row0, tid);
+  };
+  auto commit = [&](int st) {
+    if (tid < 2 * kQStep) (&s_stat[st][0][0])[tid] = -pre_stat;   // negated: the accumulators start from them
+  };
+
+  Step d_s, d_n;                                        // the step whose scores come next, the step to stage
+  next_step(d_s);                                       // a key tile always has at least its own rows
+  stage(d_s, 0);
+  commit(0);
+  bool have_s = true;
+  {
+    const TileSource srcV = make_tile_source<kD, 256>(v, it.kv_row0, Hkv, hk, T, tid);
+    stage_tile<kD, kKeys, 256>(lds + kVBase, srcV, 0, tid);
+  }
+  bf16x8 kf[2][kNKS];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const size_t off = ((size_t)min(kv0w + 32 * kb + l32, T - 1) * Hkv + hk) * kD + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < kNKS; ++ks) {
+      kf[kb][ks] = scale8(*reinterpret_cast<const bf16x8*>(k + off + 16 * ks), scale * kLog2e);
+      __builtin_amdgcn_sched_barrier(0);              // one fragment at a time: this set-up code must not need many registers
+    }
+  }
+  // pq[]: row-fragment addresses in the stage of the step whose scores are computed next; pqt[][]:
+  // transposed-fragment addresses in the stage of the step whose gradients are computed next.  Both move
+  // one stage per iteration (with wrap-around), so every LDS offset in the products is an immediate.
+  lds_cptr pq[kNKS], pqt[kNDB][2];
+#pragma unroll
+  for (int ks = 0; ks < kNKS; ++ks) pq[ks] = lds_row_ptr<kD>(lds, l32, 16 * ks + 8 * half);
+#pragma unroll
+  for (int db = 0; db < kNDB; ++db) lds_tr_ptrs<kD>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
+  int v_rel = kVBase + wave * 64 * kRowBytes;           // the swizzle of row 64 w + 32 kb + l32 equals that of row l32
+  floatx16 dk[2][kNDB], dv[2][kNDB];                    // started by the first iteration's products
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  // masks of a step for this wave: local rows [rel_lo0 (+32 for the second key block), rel_hi) minus
+  // 4*half contribute; `masked` (wave-uniform): some row of the step is masked
+  struct Mask { int rel_lo0, rel_hi; bool masked; };
+  auto masks = [&](const Step& d) -> Mask {
+    return Mask{kv0w + l32 - d.i0 - 4 * half, d.hi - d.i0 - 4 * half, !(d.i0 >= kv0w + 63 && d.i0 + kQStep <= d.hi)};
+  };
+  Mask m_s = masks(d_s), m_n = m_s;
+  const int wave_off = __builtin_amdgcn_readfirstlane((tid >> 6) * 1024);   // this wave's lines within a staging pass
+
+  // One loop body for everything.  Iteration: score products of step d_s (tiles in stage st_s, where pq
+  // points); gradient products of the step before it (tiles in the stage where pqt points; its P, dS in
+  // pf, ds) with the element-wise work of d_s spread between them.  Each wave is alone on its SIMD, so
+  // every instruction that is not issued while a product runs costs its full issue time: the walk to
+  // the step after next, the loads that stage it into st_n, its masks and the moves of the fragment
+  // addresses are cut into pieces of a few instructions, one piece behind each score product (the
+  // element-wise work fills the slots behind the gradient products).  The first iteration has no step
+  // before: pf, ds are zero and pqt points at stage 0 (finite numbers times zero).  The last iteration
+  // has no d_s: scores and element-wise work run on the stale tile of stage st_s and nobody uses them.
+  // Stage st_n's last readers (the gradient products two iterations back) finished before the barrier
+  // that ended the previous iteration.
+  uintx4 pf[2][2], ds[2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) { pf[kb][h2] = uintx4{0u, 0u, 0u, 0u}; ds[kb][h2] = uintx4{0u, 0u, 0u, 0u}; }
+  int st_s = 0;
+  int dt_pend = 0;                                      // pqt's move to the stage scored last, applied in the next score phase
+  bool again;
+#ifdef DK128_TIMING
+  auto stamp = [] { unsigned long long t; asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)); return (long long)t; };
+  long long tacc[5] = {0, 0, 0, 0, 0}, tprev = stamp(), tbegin = tprev, wbegin = wall_clock64();
+  int n_it = 0;
+#define DK128_STAMP(i) { const long long t_ = stamp(); tacc[i] += t_ - tprev; tprev = t_; }
+#else
+#define DK128_STAMP(i)
+#endif
+  auto iteration = [&](auto first_c) {
+    constexpr bool first = decltype(first_c)::value != 0;
+    const int st_n = st_s == 2 ? 0 : st_s + 1;
+    const int dq_ = st_s == 2 ? -2 * kStageBytes : kStageBytes;   // pq's move to the next stage
+    bool have_n = false;
+    int voff_n = 0, soff_n = 0, stat_r = 0;
+    const int m0_n = st_n * kStageBytes + wave_off;     // where this wave's lines of the first pass go
+    auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
+      constexpr int k = decltype(kc)::value;
+#ifdef DK128_TIMING
+      if constexpr (k == 100) DK128_STAMP(4)
+#endif
+      if constexpr (k < 4) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
+      if constexpr (k == 4) have_n = have_s && next_step(d_n);
+      if constexpr (k == 6) stat_r = min(d_n.i0 + (tid & (kQStep - 1)), T - 1);
+      if constexpr (k == 7) {
+        if (have_n && tid < 2 * kQStep) pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)d_n.head * T + stat_r];
+      }
+      if constexpr (k == 8) {
+        voff_n = srcQ.voff + d_n.head * kRowBytes;      // the Q and dO sources differ in their descriptors only
+        soff_n = (d_n.i0 - it.kv_row0) * srcQ.row_bytes;
+      }
+      if constexpr (k >= 9 && k < 13) {                  // one load each: [Q pass 0, Q pass 1, dO pass 0, dO pass 1]
+        constexpr int tile = (k - 9) >> 1, pass = (k - 9) & 1;
+        if (have_n)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes + pass * 4096, 16,
+                                                   voff_n, soff_n + pass * 16 * srcQ.row_bytes, 0, 0);
+      }
+      if constexpr (k == 13) m_n = masks(d_n);
+      if constexpr (k >= 24 && k < 32) lds_ptr_add(pq[k - 24], dq_);
+      if constexpr (k == 31) v_rel -= dq_;
+    };
+    DK128_STAMP(0)
+    floatx16 s[2], dp[2];
+    uintx4 npf[2][2], nds[2][2];
+    const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
+    score_products(pq, v_rel, (LDS_PTR(const float))s_stat[st_s][0], (LDS_PTR(const float))s_stat[st_s][1], kf, s, dp, half,
+                   m_s.masked, rel_lo, m_s.rel_hi, between);
+    DK128_STAMP(1)
+    gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) { pf[kb][h2] = npf[kb][h2]; ds[kb][h2] = nds[kb][h2]; }
+    DK128_STAMP(2)
+    if (have_n) commit(st_n);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    DK128_STAMP(3)
+    again = have_s;
+    d_s = d_n;
+    m_s = m_n;
+    have_s = have_n;
+    dt_pend = first ? 0 : (st_s == 0 ? -2 * kStageBytes : kStageBytes);   // pqt moves to the stage just scored
+    st_s = st_n;
+    // the last products' results must have landed before any vector instruction reads them (the
+    // compiler does not know that the asm statements are matrix products): explicit wait states
+    if (!again) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
+  };
+  iteration(IC<1>{});
+  while (again) {
+    iteration(IC<0>{});
+#ifdef DK128_TIMING
+    ++n_it;
+#endif
+  }
+#ifdef DK128_TIMING
+  if ((blockIdx.x == 0 || blockIdx.x == 300) && tid == 0) {
+    const long long tt = stamp() - tbegin, ww = wall_clock64() - wbegin;
+    printf("block %d: %d iterations, cycles/iter: stage %lld init %lld score %lld grad %lld barrier %lld | total %lld cycles, %lld wall ticks (100 MHz) -> %.3f GHz\n",
+           (int)blockIdx.x, n_it, tacc[0] / n_it, tacc[4] / n_it, tacc[1] / n_it, tacc[2] / n_it, tacc[3] / n_it, tt, ww, (double)tt / (double)ww * 0.1);
+  }
+#endif
+
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int my_key = kv0w + 32 * kb + l32;
+    if (it.slot >= 0) {
+      // one part of a divided key tile: fp32 partial tile [slot][kv head][dK, dV][256 rows][D]
+      float* pk_ = parts + ((size_t)it.slot * Hkv + hk) * (2 * kKeys * kD) + (size_t)(64 * wave + 32 * kb + l32) * kD;
+      float* pv_ = pk_ + kKeys * kD;
+#pragma unroll
+      for (int db = 0; db < kNDB; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int off = 32 * db + 8 * gq + 4 * half;
+          floatx4 a, b;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) { a[x] = dk[kb][db][4 * gq + x] * scale; b[x] = dv[kb][db][4 * gq + x]; }
+          *reinterpret_cast<floatx4*>(pk_ + off) = a;
+          *reinterpret_cast<floatx4*>(pv_ + off) = b;
+        }
+    } else if (my_key < kv_end) {
+      const size_t base = ((size_t)my_key * Hkv + hk) * kD;
+#pragma unroll
+      for (int db = 0; db < kNDB; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const size_t off = base + 32 * db + 8 * gq + 4 * half;
+          floatx4 a, b;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) { a[x] = dk[kb][db][4 * gq + x] * scale; b[x] = dv[kb][db][4 * gq + x]; }
+          if (load_acc) {
+            a += *reinterpret_cast<const floatx4*>(acc_dk + off);
+            b += *reinterpret_cast<const floatx4*>(acc_dv + off);
+          }
+          if (store_final) {
+            bf16x4 wa, wb;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) { wa[x] = (bf16)a[x]; wb[x] = (bf16)b[x]; }
+            *reinterpret_cast<bf16x4*>(dK + off) = wa;
+            *reinterpret_cast<bf16x4*>(dV + off) = wb;
+          } else {
+            *reinterpret_cast<floatx4*>(acc_dk + off) = a;
+            *reinterpret_cast<floatx4*>(acc_dv + off) = b;
+          }
+        }
+    }
+  }
+}
+
+}  // namespace
+
+int launch_bwd_dkdv128_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                            const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
+                            int n_items, const Seg* segs, int load_acc, int store_final, float* parts) {
+  if (n_items == 0) return 0;
+  const slimattn_params& p = *c.p;
+  const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
+  hipLaunchKernelGGL(dkdv128_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                     (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items, segs,
+                     (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+  return (int)hipGetLastError();
+}
+
+}  // namespace slimattn

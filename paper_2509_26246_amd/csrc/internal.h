@@ -32,10 +32,13 @@ struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end, slot, pad0, pad1, 
 // A divided key tile: partial tiles first_slot .. first_slot + n_parts - 1 are its parts.
 struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts; };
 
-// Divided lists exist for the 128-row key tile and four classes of KV-head count (1, 2, 4, >= 8):
-// a launch has items x KV heads blocks, so the fewer KV heads, the fewer blocks share the work and
-// the more a single long sample's first tiles dominate the makespan.
-constexpr int kSplitTileRows = 128;
+// Divided lists exist for the 128- and 256-row key tiles (the two bf16 dK/dV kernels) and four classes
+// of KV-head count (1, 2, 4, >= 8): a launch has items x KV heads blocks, so the fewer KV heads, the
+// fewer blocks share the work and the more a single long sample's first tiles dominate the makespan.
+constexpr int kNumSplitTiles = 2;
+constexpr int kSplitTileRows[kNumSplitTiles] = {128, 256};
+constexpr int kSplitBlockSlots[kNumSplitTiles] = {512, 256};   // resident blocks of the kernel that uses the tile
+inline int split_tile_index(int rows) { return rows == 128 ? 0 : rows == 256 ? 1 : -1; }
 constexpr int kNumSplitClasses = 4;
 inline int split_class(int n_kv_heads) { return n_kv_heads >= 8 ? 3 : n_kv_heads >= 4 ? 2 : n_kv_heads >= 2 ? 1 : 0; }
 
@@ -46,20 +49,20 @@ struct ScopeLists {
   std::vector<int32_t> kv_off[kNumTileSizes];
   std::vector<KvItem> kv_items[kNumTileSizes];
   std::vector<Seg> segs;                        // all units' runs (and the parts' cut runs), referenced by the items
-  // 128-row key tiles with heavy tiles divided, per KV-head class; same unit-major layout
-  std::vector<int32_t> split_off[kNumSplitClasses];
-  std::vector<KvItem> split_items[kNumSplitClasses];
-  std::vector<int32_t> reduce_off[kNumSplitClasses];
-  std::vector<KvReduce> reduce_items[kNumSplitClasses];
-  int32_t max_slots[kNumSplitClasses] = {0, 0, 0, 0};   // most partial tiles any one scope needs
+  // key tiles with heavy tiles divided, per tile size and KV-head class; same unit-major layout
+  std::vector<int32_t> split_off[kNumSplitTiles][kNumSplitClasses];
+  std::vector<KvItem> split_items[kNumSplitTiles][kNumSplitClasses];
+  std::vector<int32_t> reduce_off[kNumSplitTiles][kNumSplitClasses];
+  std::vector<KvReduce> reduce_items[kNumSplitTiles][kNumSplitClasses];
+  int32_t max_slots[kNumSplitTiles][kNumSplitClasses] = {{0, 0, 0, 0}, {0, 0, 0, 0}};   // most partial tiles any one scope needs
 };
 
 struct DeviceLists {                            // device mirrors (pointers into one allocation)
   const QItem* q_items[kNumTileSizes];
   const KvItem* kv_items[kNumTileSizes];
   const Seg* segs;
-  const KvItem* split_items[kNumSplitClasses];
-  const KvReduce* reduce_items[kNumSplitClasses];
+  const KvItem* split_items[kNumSplitTiles][kNumSplitClasses];
+  const KvReduce* reduce_items[kNumSplitTiles][kNumSplitClasses];
 };
 
 }  // namespace slimattn
@@ -108,14 +111,23 @@ int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const voi
 int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
                          int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
-// adds up the partial tiles of divided key tiles (in slot order) into dK/dV or the fp32 accumulators
+// head_dim 128: one wave per SIMD, 256 key rows per block (dkdv128_bf16.hip); same arguments
+int launch_bwd_dkdv128_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
+                            const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
+                            int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
+// adds up the partial tiles (tile_rows rows each) of divided key tiles, in slot order, into dK/dV or the
+// fp32 accumulators
 int launch_bwd_reduce_bf16(const LaunchCtx&, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
-                           const KvReduce* items, int n_items, int load_acc, int store_final);
+                           const KvReduce* items, int n_items, int load_acc, int store_final, int tile_rows);
 int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);
 
 // Tile sizes each kernel family uses (must be one of kTileSizes).
 int fwd_q_tile(int dtype, int head_dim);
 int dq_q_tile(int dtype, int head_dim);
 int dkdv_kv_tile(int dtype, int head_dim);
+// Which dK/dV kernel a bf16 problem uses: the 256-key kernel with one wave per SIMD (head dim 128
+// only) or the 128-key kernel.  One switch for the launch code and for the choice of the tile lists.
+constexpr bool kDkdv128Enabled = false;
+inline bool use_dkdv128(int dtype, int head_dim) { return kDkdv128Enabled && dtype == SLIMATTN_BF16 && head_dim == 128; }
 
 }  // namespace slimattn

@@ -230,8 +230,29 @@ __device__ __forceinline__ void r2_issue_wait(lds_cptr a0, lds_cptr a1, R2& n, R
 }
 __device__ __forceinline__ void r2_wait(R2& p) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.f[0]), "+v"(p.f[1])); }
 
+// Four-fragment row batches.
+struct R4 { bf16x8 f[4]; };
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void r4_issue(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n) {
+  asm volatile("ds_read_b128 %0, %[a0] offset:%[o0]\n\tds_read_b128 %1, %[a1] offset:%[o1]\n\t"
+               "ds_read_b128 %2, %[a2] offset:%[o2]\n\tds_read_b128 %3, %[a3] offset:%[o3]"
+               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3])
+               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
+                 [o3] "n"(O3));
+}
+
+// One row fragment (for code that spreads a batch's reads between other instructions).
+template <int O>
+__device__ __forceinline__ void r1_issue(lds_cptr a, bf16x8& f) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(f) : "v"(a), "n"(O));
+}
+
 // Wait until at most N LDS operations issued by this wave are outstanding; `p` (a batch issued
 // before those N) is then complete, and its consumers are ordered after the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait(R4& p) {
+  asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]), "+v"(p.f[2]), "+v"(p.f[3]) : [n] "n"(N));
+}
 template <int N>
 __device__ __forceinline__ void lds_wait(R2& p) {
   asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(p.f[0]), "+v"(p.f[1]) : [n] "n"(N));

@@ -45,10 +45,10 @@ std::vector<Run> merge_runs(const slimattn_slice* sl, const int32_t* ids, int32_
 // than kMinPartRows).  A part is an item of
 // its own, with its own (cut) runs appended to segs and a partial-tile slot; slots of one tile are
 // consecutive and the reduction adds them in that order, so results do not depend on scheduling.
-constexpr int kBlockSlots = 512;          // 256 compute units x 2 resident blocks
 constexpr int64_t kMinPartRows = 1024;
 
-void append_split(ScopeLists& L, const std::vector<KvItem>& ki, const std::vector<int64_t>& weight) {
+void append_split(ScopeLists& L, int ti, const std::vector<KvItem>& ki, const std::vector<int64_t>& weight) {
+  const int64_t kBlockSlots = kSplitBlockSlots[ti];
   int64_t total = 0;
   for (int64_t w : weight) total += w;
   for (int c = 0; c < kNumSplitClasses; ++c) {
@@ -69,8 +69,8 @@ void append_split(ScopeLists& L, const std::vector<KvItem>& ki, const std::vecto
         continue;
       }
       const int64_t chunk = ((weight[x] + parts - 1) / parts + 127) / 128 * 128;
-      L.reduce_items[c].push_back(KvReduce{ki[x].kv_row0, ki[x].kv_rows, slots, 0});
-      KvReduce& red = L.reduce_items[c].back();
+      L.reduce_items[ti][c].push_back(KvReduce{ki[x].kv_row0, ki[x].kv_rows, slots, 0});
+      KvReduce& red = L.reduce_items[ti][c].back();
       // walk the tile's runs, closing a part whenever it holds `chunk` rows
       int64_t have = 0;
       int32_t part_seg_begin = (int32_t)L.segs.size();
@@ -98,10 +98,10 @@ void append_split(ScopeLists& L, const std::vector<KvItem>& ki, const std::vecto
     std::vector<int32_t> order(items.size());
     for (size_t x = 0; x < order.size(); ++x) order[x] = (int32_t)x;
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return w[a] > w[b]; });
-    for (int32_t x : order) L.split_items[c].push_back(items[x]);
-    L.split_off[c].push_back((int32_t)L.split_items[c].size());
-    L.reduce_off[c].push_back((int32_t)L.reduce_items[c].size());
-    L.max_slots[c] = std::max(L.max_slots[c], slots);
+    for (int32_t x : order) L.split_items[ti][c].push_back(items[x]);
+    L.split_off[ti][c].push_back((int32_t)L.split_items[ti][c].size());
+    L.reduce_off[ti][c].push_back((int32_t)L.reduce_items[ti][c].size());
+    L.max_slots[ti][c] = std::max(L.max_slots[ti][c], slots);
   }
 }
 
@@ -142,7 +142,7 @@ void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return weight[a] > weight[b]; });
     for (int32_t x : order) L.kv_items[z].push_back(ki[x]);
     L.kv_off[z].push_back((int32_t)L.kv_items[z].size());
-    if (B == kSplitTileRows) append_split(L, ki, weight);
+    if (split_tile_index(B) >= 0) append_split(L, split_tile_index(B), ki, weight);
   }
 }
 
@@ -194,7 +194,8 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     t->unit_slices[1].assign(bwd_unit_slices, bwd_unit_slices + n_slices);
     for (int pass = 0; pass < 2; ++pass) {
       for (int z = 0; z < kNumTileSizes; ++z) { t->per_unit[pass].q_off[z].push_back(0); t->per_unit[pass].kv_off[z].push_back(0); }
-      for (int c = 0; c < kNumSplitClasses; ++c) { t->per_unit[pass].split_off[c].push_back(0); t->per_unit[pass].reduce_off[c].push_back(0); }
+      for (int ti = 0; ti < kNumSplitTiles; ++ti)
+        for (int c = 0; c < kNumSplitClasses; ++c) { t->per_unit[pass].split_off[ti][c].push_back(0); t->per_unit[pass].reduce_off[ti][c].push_back(0); }
       for (int32_t u = 0; u < t->n_units[pass]; ++u) {
         const int32_t a = t->unit_ptr[pass][u], b = t->unit_ptr[pass][u + 1];
         append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a));
@@ -203,13 +204,14 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     std::vector<int32_t> all(n_slices);
     for (int32_t i = 0; i < n_slices; ++i) all[i] = i;
     for (int z = 0; z < kNumTileSizes; ++z) { t->fused.q_off[z].push_back(0); t->fused.kv_off[z].push_back(0); }
-    for (int c = 0; c < kNumSplitClasses; ++c) { t->fused.split_off[c].push_back(0); t->fused.reduce_off[c].push_back(0); }
+    for (int ti = 0; ti < kNumSplitTiles; ++ti)
+      for (int c = 0; c < kNumSplitClasses; ++c) { t->fused.split_off[ti][c].push_back(0); t->fused.reduce_off[ti][c].push_back(0); }
     append_scope(t->fused, merge_runs(slices, all.data(), n_slices));
 
     // one blob, one upload
     std::vector<char> blob;
     const size_t off_cu = place(blob, t->cu), off_sl = place(blob, t->slices);
-    size_t off_q[3][kNumTileSizes], off_kv[3][kNumTileSizes], off_seg[3], off_sp[3][kNumSplitClasses], off_rd[3][kNumSplitClasses];
+    size_t off_q[3][kNumTileSizes], off_kv[3][kNumTileSizes], off_seg[3], off_sp[3][kNumSplitTiles][kNumSplitClasses], off_rd[3][kNumSplitTiles][kNumSplitClasses];
     ScopeLists* lists[3] = {&t->per_unit[0], &t->per_unit[1], &t->fused};
     for (int s = 0; s < 3; ++s) {
       for (int z = 0; z < kNumTileSizes; ++z) {
@@ -217,10 +219,11 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
         off_kv[s][z] = place(blob, lists[s]->kv_items[z]);
       }
       off_seg[s] = place(blob, lists[s]->segs);
-      for (int c = 0; c < kNumSplitClasses; ++c) {
-        off_sp[s][c] = place(blob, lists[s]->split_items[c]);
-        off_rd[s][c] = place(blob, lists[s]->reduce_items[c]);
-      }
+      for (int ti = 0; ti < kNumSplitTiles; ++ti)
+        for (int c = 0; c < kNumSplitClasses; ++c) {
+          off_sp[s][ti][c] = place(blob, lists[s]->split_items[ti][c]);
+          off_rd[s][ti][c] = place(blob, lists[s]->reduce_items[ti][c]);
+        }
     }
     blob.resize(align_up(blob.size()) + 256);
     hipError_t e = hipGetDevice(&t->device);
@@ -242,10 +245,11 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
         dl[s]->kv_items[z] = (const KvItem*)(base + off_kv[s][z]);
       }
       dl[s]->segs = (const Seg*)(base + off_seg[s]);
-      for (int c = 0; c < kNumSplitClasses; ++c) {
-        dl[s]->split_items[c] = (const KvItem*)(base + off_sp[s][c]);
-        dl[s]->reduce_items[c] = (const KvReduce*)(base + off_rd[s][c]);
-      }
+      for (int ti = 0; ti < kNumSplitTiles; ++ti)
+        for (int c = 0; c < kNumSplitClasses; ++c) {
+          dl[s]->split_items[ti][c] = (const KvItem*)(base + off_sp[s][ti][c]);
+          dl[s]->reduce_items[ti][c] = (const KvReduce*)(base + off_rd[s][ti][c]);
+        }
     }
   } catch (const std::bad_alloc&) {
     delete t;
@@ -269,7 +273,8 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
     case 2: return t->n_slices;
     case 3: return t->n_units[0];
     case 4: return t->n_units[1];
-    case 5: case 6: case 7: case 8: return (int64_t)t->fused.reduce_items[what - 5].size();
+    case 5: case 6: case 7: case 8: return (int64_t)t->fused.reduce_items[0][what - 5].size();
+    case 9: case 10: case 11: case 12: return (int64_t)t->fused.reduce_items[1][what - 9].size();
     default: return -1;
   }
 }
@@ -278,8 +283,11 @@ size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_
   if (!t || hq < 1 || hkv < 1 || d < 1) return 0;
   const size_t T = (size_t)t->total_tokens;
   const int c = split_class(hkv);
-  const size_t slots = (size_t)std::max({t->per_unit[0].max_slots[c], t->per_unit[1].max_slots[c], t->fused.max_slots[c]});
-  const size_t parts = slots * hkv * 2 * kSplitTileRows * d * sizeof(float);
+  size_t parts = 0;                       // the larger of the two tile sizes' needs (which kernel runs depends on dtype, d)
+  for (int ti = 0; ti < kNumSplitTiles; ++ti) {
+    const size_t slots = (size_t)std::max({t->per_unit[0].max_slots[ti][c], t->per_unit[1].max_slots[ti][c], t->fused.max_slots[ti][c]});
+    parts = std::max(parts, slots * hkv * 2 * kSplitTileRows[ti] * d * sizeof(float));
+  }
   return align_up(2 * T * hkv * d * sizeof(float)) + 2 * align_up(T * hq * sizeof(float)) + align_up(parts) + 256;
 }
 
