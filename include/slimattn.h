@@ -154,8 +154,8 @@ void slimattn_tables_destroy(slimattn_tables* t);
  * informational). */
 int64_t slimattn_tables_count(const slimattn_tables* t, int what);
 
-/* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators, two per-row statistics,
- * partial tiles of divided key tiles). */
+/* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators, the per-row statistics in
+ * fp32 and as bf16 triples, partial tiles of divided key tiles). */
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t n_q_heads, int32_t n_kv_heads,
                                     int32_t head_dim);
 

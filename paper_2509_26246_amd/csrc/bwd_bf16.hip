@@ -29,10 +29,22 @@ template <int D> struct DkdvCfg { static constexpr int kQStep = D == 128 ? 32 : 
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------------
+// x as three bf16 terms (w[at], w[at + 1], w[at + 2]) whose sum is x to fp32 precision
+__device__ __forceinline__ void split3(float x, bf16x8& w, int at) {
+  const bf16 a = (bf16)x;
+  float r = x - (float)a;
+  const bf16 b = (bf16)r;
+  r -= (float)b;
+  w[at] = a;
+  w[at + 1] = b;
+  w[at + 2] = (bf16)r;
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, float* __restrict__ delta,
-                                                         float* __restrict__ lse2, int T, int Hq) {
+                                                         float* __restrict__ lse2, bf16x8* __restrict__ stat3, int T,
+                                                         int Hq) {
   constexpr int LPR = D / 8;                                   // lanes per (row, head)
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t rh = idx / LPR;                                // row * Hq + head
@@ -49,7 +61,18 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const bf16* __restrict_
   if (live && (idx % LPR) == 0) {
     const size_t at = (size_t)(rh % Hq) * T + (rh / Hq);
     delta[at] = s;
-    lse2[at] = lse[at] * kLog2e;                                // the row statistic in log2 units, for exp2
+    const float l2 = lse[at] * kLog2e;                          // the row statistic in log2 units, for exp2
+    lse2[at] = l2;
+    if (stat3) {
+      // -lse2 and -delta, each as three bf16 terms whose sum is the fp32 value (8 significand bits per
+      // term): a matrix product with a fragment of ones adds them into an accumulator exactly
+      bf16x8 w;
+      split3(-l2, w, 0);
+      split3(-s, w, 4);
+      w[3] = (bf16)0.f;
+      w[7] = (bf16)0.f;
+      stat3[at] = w;
+    }
   }
 }
 
@@ -511,17 +534,18 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
 int dkdv_kv_tile(int dtype, int head_dim) { return dtype == SLIMATTN_F32 ? 64 : use_dkdv128(dtype, head_dim) ? 256 : kKvOwn; }
 
-int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2) {
+int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2,
+                          void* stat3) {
   const slimattn_params& p = *c.p;
   const int64_t n = c.T * p.n_q_heads * (p.head_dim / 8);
   if (n == 0) return 0;
   const dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(delta_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse, delta,
-                       lse2, (int)c.T, p.n_q_heads);
+                       lse2, (bf16x8*)stat3, (int)c.T, p.n_q_heads);
   else
     hipLaunchKernelGGL(delta_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse, delta,
-                       lse2, (int)c.T, p.n_q_heads);
+                       lse2, (bf16x8*)stat3, (int)c.T, p.n_q_heads);
   return (int)hipGetLastError();
 }
 

@@ -55,32 +55,43 @@ __device__ __forceinline__ void mfma_acc(floatx16& acc, bf16x8 a, bf16x8 b) {
 // Score products of one step: s[kb] = Q K_kb^T - lse (log2 units, kf holds k * scale * log2 e),
 // dp[kb] = dO V_kb^T - delta, for the wave's two key blocks.  pq[] point at the step's Q tile (the dO
 // tile follows it), v_rel is the byte distance from there to this wave's V rows.  The accumulators
-// start at minus the row statistics (local row of register r: 8 (r/4) + 4 half + r%4); where the row
-// lies before the lane's key or at/after the end of the query run (local rows outside
-// [rel_lo[kb], rel_hi), `masked` steps only) the score starts at -inf, so that its probability and
-// its dS come out as zero.  One batch of LDS reads per head-dim step: the Q and dO fragments and the two
-// V fragments.
+// start at minus the row statistics: `stat` holds, for the lane's row (l32), -lse2 and -delta as three
+// bf16 terms each ({l, l, l, 0, d, d, d, 0}; the terms of a triple add up to the fp32 value), and a
+// product with a fragment of ones (ones_l picks the first triple, ones_d the second; zero in the upper
+// half-wave, whose copy of `stat` therefore does not count) puts their sums into every column of the
+// row.  That costs four products and no vector or LDS instruction, where loading the 64 accumulator
+// registers costs a quarter of the phase.  In `masked` steps the scores of pairs that do not count
+// (local row - 4*half outside [rel_lo[kb], rel_hi): before the lane's key, or past the end of the query
+// run) are then set to -inf, so that their probability and dS come out as zero.  One batch of LDS
+// reads per head-dim step: the Q and dO fragments and the two V fragments.
 template <class Between>
-__device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v_rel, LDS_PTR(const float) s_lse, LDS_PTR(const float) s_delta,
-                                               const bf16x8 (&kf)[2][kNKS], floatx16 (&s)[2], floatx16 (&dp)[2], int half,
+__device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v_rel, bf16x8 stat, uintx4 ones_l, uintx4 ones_d,
+                                               const bf16x8 (&kf)[2][kNKS], floatx16 (&s)[2], floatx16 (&dp)[2],
                                                bool masked, const int (&rel_lo)[2], int rel_hi, Between&& between) {
-  // the statistics are stored negated; every accumulator quad gets an LDS read of its own (volatile:
-  // a shared read plus register copies would cost vector instructions that nothing overlaps)
-#pragma unroll
-  for (int gq = 0; gq < 4; ++gq) {
-    LDS_PTR(const volatile floatx4) pl = (LDS_PTR(const volatile floatx4))(s_lse + 8 * gq + 4 * half);
-    LDS_PTR(const volatile floatx4) pd = (LDS_PTR(const volatile floatx4))(s_delta + 8 * gq + 4 * half);
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const floatx4 l4 = *pl, d4 = *pd;
-#pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        s[kb][4 * gq + x] = l4[x];
-        dp[kb][4 * gq + x] = d4[x];
-      }
-    }
-  }
+  // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
+  // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
+  // issue time of a plain instruction: four in a row would outlast the product they follow); those of
+  // the first two steps run while the accumulators are started.
+  R4 g[kNKS];
+  lds_cptr pv = pq[0];
+  auto issue_one = [&](auto uc, auto ic) {
+    constexpr int u = decltype(uc)::value, i = decltype(ic)::value;
+    if constexpr (i == 0) r1_issue<0>(pq[u], g[u].f[0]);
+    if constexpr (i == 1) { r1_issue<kTileBytes>(pq[u], g[u].f[1]); pv = pq[u] + v_rel; }
+    if constexpr (i == 2) r1_issue<0>(pv, g[u].f[2]);
+    if constexpr (i == 3) r1_issue<32 * kRowBytes>(pv, g[u].f[3]);
+  };
+  static_for<0, 4>([&](auto ic) { issue_one(IC<0>{}, ic); });
+  // asm: two of the four products are equal and the compiler would compute them once and copy
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s[0]) : "v"(stat), "v"(ones_l));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s[1]) : "v"(stat), "v"(ones_l));
+  static_for<0, 4>([&](auto ic) { issue_one(IC<1>{}, ic); });
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(dp[0]) : "v"(stat), "v"(ones_d));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(dp[1]) : "v"(stat), "v"(ones_d));
   if (masked) {
+    // the products above are asm statements: the compiler does not separate them from readers of
+    // their results by the wait states the hardware needs
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       const unsigned span = (unsigned)max(rel_hi - rel_lo[kb], 0);   // c - rel_lo in [0, span) <=> the pair counts
@@ -95,23 +106,10 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(s[0]), "+v"(s[1]), "+v"(dp[0]), "+v"(dp[1]));
   between(IC<100>{});
 #endif
-  // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
-  // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
-  // issue time of a plain instruction: four in a row would outlast the product they follow).
-  R4 g[kNKS];
-  lds_cptr pv = pq[0];
-  auto issue_one = [&](auto uc, auto ic) {
-    constexpr int u = decltype(uc)::value, i = decltype(ic)::value;
-    if constexpr (i == 0) r1_issue<0>(pq[u], g[u].f[0]);
-    if constexpr (i == 1) { r1_issue<kTileBytes>(pq[u], g[u].f[1]); pv = pq[u] + v_rel; }
-    if constexpr (i == 2) r1_issue<0>(pv, g[u].f[2]);
-    if constexpr (i == 3) r1_issue<32 * kRowBytes>(pv, g[u].f[3]);
-  };
-  static_for<0, 2>([&](auto uc) { static_for<0, 4>([&](auto ic) { issue_one(uc, ic); }); });
   static_for<0, kNKS>([&](auto uc) {
     constexpr int u = decltype(uc)::value;
     constexpr bool more = u + 2 < kNKS;
-    lds_wait<(u + 1 < kNKS) ? 4 : 0>(g[u]);
+    lds_wait<4>(g[u]);                                  // behind step u: step u + 1 or, at the end, a batch of gradient reads
     s[0] = mfma32(g[u].f[0], kf[0][u], s[0]);
     if constexpr (more) issue_one(IC<u + 2>{}, IC<0>{});
     between(IC<4 * u + 0>{});
@@ -176,6 +174,15 @@ __device__ __forceinline__ void ew_slot(floatx16 (&s)[2], floatx16 (&dp)[2], uin
   }
 }
 
+// Read i (of four) of gradient batch B: the dO^T fragment (reads 0, 1) and the Q^T fragment (2, 3) of
+// head-dim block B % 4, rows 16 (B / 4) .. +16 of the step's tiles.
+constexpr int kGradBatches = 2 * kNDB;
+template <int B, int I>
+__device__ __forceinline__ void grad_read(const lds_cptr (&pqt)[kNDB][2], Tr2 (&tb)[kGradBatches]) {
+  constexpr int st = B / kNDB, db = B % kNDB;
+  tr1_issue<st * 16 * kRowBytes + (I < 2 ? kTileBytes : 0)>(pqt[db][I & 1], tb[B].r[I]);
+}
+
 // Gradient products of one step, dV_kb^T += dO^T P_kb and dK_kb^T += Q^T dS_kb, with P, dS packed in
 // pf[kb][half16], ds[kb][half16]; pqt[][] point at the step's Q tile.  Per head-dim block and 16-row half
 // one batch of two transposed fragments (dO^T, Q^T), each feeding both key blocks.  The element-wise work
@@ -185,30 +192,29 @@ template <bool FIRST>
 __device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB][2], const uintx4 (&pf)[2][2],
                                                   const uintx4 (&ds)[2][2], floatx16 (&dk)[2][kNDB], floatx16 (&dv)[2][kNDB],
                                                   floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2],
-                                                  uintx4 (&nds)[2][2]) {
-  constexpr int NB = 2 * kNDB;
-  Tr2 tb[NB];
-  auto issue = [&](auto ic) {
+                                                  uintx4 (&nds)[2][2], Tr2 (&tb)[kGradBatches]) {
+  // batch b: head-dim block b % 4 of 16-row half b / 4 (first half first: its P, dS die early); its
+  // four reads are issued one behind each product of batch b - 2, those of batches 0 and 1 behind the
+  // last score products (by the caller)
+  static_for<0, kGradBatches>([&](auto ic) {
     constexpr int b = decltype(ic)::value, st = b / kNDB, db = b % kNDB;
-    tr2_issue<st * 16 * kRowBytes + kTileBytes, st * 16 * kRowBytes>(pqt[db][0], pqt[db][1], tb[b]);
-  };
-  static_for<0, 2>(issue);
-  static_for<0, NB>([&](auto ic) {
-    constexpr int b = decltype(ic)::value, st = b / kNDB, db = b % kNDB;   // first 16-row half first: its P, dS die early
-    constexpr int behind = 4 * ((NB - 1 - b) < 2 ? (NB - 1 - b) : 2);
-    if constexpr (b + 2 < NB) issue(IC<b + 2>{});
-    lds_wait<behind>(tb[b]);
+    constexpr bool more = b + 2 < kGradBatches;
+    lds_wait<(b + 1 < kGradBatches) ? 4 : 0>(tb[b]);
     constexpr bool kStart = FIRST && st == 0;
     mfma_acc<kStart>(dv[0][db], tr2_frag(tb[b], 0), as_frag(pf[0][st]));
+    if constexpr (more) grad_read<b + 2, 0>(pqt, tb);
     ew_slot<4 * b + 0>(s, dp, npf, nds);
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dv[1][db], tr2_frag(tb[b], 0), as_frag(pf[1][st]));
+    if constexpr (more) grad_read<b + 2, 1>(pqt, tb);
     ew_slot<4 * b + 1>(s, dp, npf, nds);
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dk[0][db], tr2_frag(tb[b], 1), as_frag(ds[0][st]));
+    if constexpr (more) grad_read<b + 2, 2>(pqt, tb);
     ew_slot<4 * b + 2>(s, dp, npf, nds);
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dk[1][db], tr2_frag(tb[b], 1), as_frag(ds[1][st]));
+    if constexpr (more) grad_read<b + 2, 3>(pqt, tb);
     ew_slot<4 * b + 3>(s, dp, npf, nds);
     __builtin_amdgcn_sched_barrier(0);
   });
@@ -226,11 +232,10 @@ struct Step { int i0, hi, head; };                      // rows [i0, min(i0 + 32
 
 __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
-    const float* __restrict__ lse2, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
+    const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
     int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
   __shared__ __attribute__((aligned(1024))) char smem[kVBase + kVBytes];   // three [Q, dO] stages, then the V tile
-  __shared__ __attribute__((aligned(16))) float s_stat[kStages][2][kQStep];  // [stage][lse2, delta][row]
 
   const int g = Hq / Hkv;
   const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
@@ -269,26 +274,23 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
 
   const TileSource srcQ = make_tile_source<kD, 256>(q, it.kv_row0, Hq, 0, T, tid);
   const TileSource srcDO = make_tile_source<kD, 256>(dO, it.kv_row0, Hq, 0, T, tid);
-  float pre_stat = 0.f;                                 // a staged step's lse2 (threads 0..31) / delta (32..63)
-  auto stage = [&](const Step& d, int st) {             // statistics into a register, tiles straight into LDS
-    if (tid < 2 * kQStep) {
-      const int r = min(d.i0 + (tid & (kQStep - 1)), T - 1);
-      pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)d.head * T + r];
-    }
+  auto stage = [&](const Step& d, int st) {             // a step's Q and dO tiles straight into LDS
     TileSource a = srcQ, b = srcDO;
     a.voff += d.head * kRowBytes;
     b.voff += d.head * kRowBytes;
     stage_tile<kD, kQStep, 256>(lds + st * kStageBytes, a, d.i0 - it.kv_row0, tid);
     stage_tile<kD, kQStep, 256>(lds + st * kStageBytes + kTileBytes, b, d.i0 - it.kv_row0, tid);
   };
-  auto commit = [&](int st) {
-    if (tid < 2 * kQStep) (&s_stat[st][0][0])[tid] = -pre_stat;   // negated: the accumulators start from them
-  };
+  // a step's statistics for this lane's row: -lse2, -delta as bf16 triples (rows past the end are masked)
+  auto load_stat = [&](const Step& d) -> bf16x8 { return stat3[(size_t)d.head * T + min(d.i0 + l32, T - 1)]; };
 
   Step d_s, d_n;                                        // the step whose scores come next, the step to stage
   next_step(d_s);                                       // a key tile always has at least its own rows
+  d_n = d_s;
   stage(d_s, 0);
-  commit(0);
+  bf16x8 stat_s = load_stat(d_s), stat_n = stat_s;
+  const unsigned one2 = half ? 0u : 0x3F803F80u, one1 = half ? 0u : 0x00003F80u;   // bf16 {1, 1}, {1, 0}; lower half-wave only
+  const uintx4 ones_l = {one2, one1, 0u, 0u}, ones_d = {0u, 0u, one2, one1};
   bool have_s = true;
   {
     const TileSource srcV = make_tile_source<kD, 256>(v, it.kv_row0, Hkv, hk, T, tid);
@@ -358,7 +360,8 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     const int st_n = st_s == 2 ? 0 : st_s + 1;
     const int dq_ = st_s == 2 ? -2 * kStageBytes : kStageBytes;   // pq's move to the next stage
     bool have_n = false;
-    int voff_n = 0, soff_n = 0, stat_r = 0;
+    int voff_n = 0, soff_n = 0;
+    Tr2 tb[kGradBatches];                               // the gradient phase's batches of transposed fragments
     const int m0_n = st_n * kStageBytes + wave_off;     // where this wave's lines of the first pass go
     auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
       constexpr int k = decltype(kc)::value;
@@ -367,10 +370,7 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
 #endif
       if constexpr (k < 4) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
       if constexpr (k == 4) have_n = have_s && next_step(d_n);
-      if constexpr (k == 6) stat_r = min(d_n.i0 + (tid & (kQStep - 1)), T - 1);
-      if constexpr (k == 7) {
-        if (have_n && tid < 2 * kQStep) pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)d_n.head * T + stat_r];
-      }
+      if constexpr (k == 6) stat_n = load_stat(d_n);      // d_n always names a real step (the last one, when the walk has ended)
       if constexpr (k == 8) {
         voff_n = srcQ.voff + d_n.head * kRowBytes;      // the Q and dO sources differ in their descriptors only
         soff_n = (d_n.i0 - it.kv_row0) * srcQ.row_bytes;
@@ -382,29 +382,31 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
                                                    voff_n, soff_n + pass * 16 * srcQ.row_bytes, 0, 0);
       }
       if constexpr (k == 13) m_n = masks(d_n);
-      if constexpr (k >= 24 && k < 32) lds_ptr_add(pq[k - 24], dq_);
+      if constexpr (k >= 24 && k < 32) {                 // the gradient phase's first two batches of reads
+        grad_read<(k - 24) / 4, (k - 24) % 4>(pqt, tb);
+        lds_ptr_add(pq[k - 24], dq_);
+      }
       if constexpr (k == 31) v_rel -= dq_;
     };
     DK128_STAMP(0)
     floatx16 s[2], dp[2];
     uintx4 npf[2][2], nds[2][2];
     const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
-    score_products(pq, v_rel, (LDS_PTR(const float))s_stat[st_s][0], (LDS_PTR(const float))s_stat[st_s][1], kf, s, dp, half,
-                   m_s.masked, rel_lo, m_s.rel_hi, between);
+    score_products(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, m_s.rel_hi, between);
     DK128_STAMP(1)
-    gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds);
+    gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) { pf[kb][h2] = npf[kb][h2]; ds[kb][h2] = nds[kb][h2]; }
     DK128_STAMP(2)
-    if (have_n) commit(st_n);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     DK128_STAMP(3)
     again = have_s;
     d_s = d_n;
     m_s = m_n;
+    stat_s = stat_n;
     have_s = have_n;
     dt_pend = first ? 0 : (st_s == 0 ? -2 * kStageBytes : kStageBytes);   // pqt moves to the stage just scored
     st_s = st_n;
@@ -420,10 +422,10 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
 #endif
   }
 #ifdef DK128_TIMING
-  if ((blockIdx.x == 0 || blockIdx.x == 300) && tid == 0) {
-    const long long tt = stamp() - tbegin, ww = wall_clock64() - wbegin;
-    printf("block %d: %d iterations, cycles/iter: stage %lld init %lld score %lld grad %lld barrier %lld | total %lld cycles, %lld wall ticks (100 MHz) -> %.3f GHz\n",
-           (int)blockIdx.x, n_it, tacc[0] / n_it, tacc[4] / n_it, tacc[1] / n_it, tacc[2] / n_it, tacc[3] / n_it, tt, ww, (double)tt / (double)ww * 0.1);
+  if (tid == 0) {   // timing build: one record per block at the start of the (otherwise unused) fp32 accumulators
+    long long* rec = reinterpret_cast<long long*>(acc_dk) + 10 * (size_t)blockIdx.x;
+    rec[0] = n_it; rec[1] = stamp() - tbegin; rec[2] = wbegin; rec[3] = wall_clock64();
+    rec[4] = tacc[0]; rec[5] = tacc[4]; rec[6] = tacc[1]; rec[7] = tacc[2]; rec[8] = tacc[3]; rec[9] = 1;
   }
 #endif
 
@@ -476,14 +478,14 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
 
 }  // namespace
 
-int launch_bwd_dkdv128_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
-                            const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
+int launch_bwd_dkdv128_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
+                            float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
                             int n_items, const Seg* segs, int load_acc, int store_final, float* parts) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
   hipLaunchKernelGGL(dkdv128_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                     (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items, segs,
+                     (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items, segs,
                      (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
   return (int)hipGetLastError();
 }

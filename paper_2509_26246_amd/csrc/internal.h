@@ -104,7 +104,8 @@ int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
 
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
-int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, float* delta, float* lse2);
+int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, float* delta, float* lse2,
+                          void* stat3);
 // the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
 int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                        const float* delta, void* dQ, const QItem* items, int n_items);
@@ -112,9 +113,9 @@ int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const v
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
                          int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv128_bf16.hip); same arguments
-int launch_bwd_dkdv128_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
-                            const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                            int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
+int launch_bwd_dkdv128_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
+                            float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
+                            int load_acc, int store_final, float* parts);
 // adds up the partial tiles (tile_rows rows each) of divided key tiles, in slot order, into dK/dV or the
 // fp32 accumulators
 int launch_bwd_reduce_bf16(const LaunchCtx&, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
@@ -127,7 +128,10 @@ int dq_q_tile(int dtype, int head_dim);
 int dkdv_kv_tile(int dtype, int head_dim);
 // Which dK/dV kernel a bf16 problem uses: the 256-key kernel with one wave per SIMD (head dim 128
 // only) or the 128-key kernel.  One switch for the launch code and for the choice of the tile lists.
-constexpr bool kDkdv128Enabled = false;
+#ifndef SLIMATTN_DKDV128
+#define SLIMATTN_DKDV128 1
+#endif
+constexpr bool kDkdv128Enabled = SLIMATTN_DKDV128 != 0;
 inline bool use_dkdv128(int dtype, int head_dim) { return kDkdv128Enabled && dtype == SLIMATTN_BF16 && head_dim == 128; }
 
 }  // namespace slimattn

@@ -241,6 +241,13 @@ __device__ __forceinline__ void r4_issue(lds_cptr a0, lds_cptr a1, lds_cptr a2, 
                  [o3] "n"(O3));
 }
 
+// One transposed 64-bit read of a Tr2 batch (r[0], r[1]: first fragment from the two addresses of
+// the pair; r[2], r[3]: second fragment), for code that spreads the reads between other instructions.
+template <int O>
+__device__ __forceinline__ void tr1_issue(lds_cptr p, short4v& r) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=&v"(r) : "v"(p), "n"(O));
+}
+
 // One row fragment (for code that spreads a batch's reads between other instructions).
 template <int O>
 __device__ __forceinline__ void r1_issue(lds_cptr a, bf16x8& f) {
