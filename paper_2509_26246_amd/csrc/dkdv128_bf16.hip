@@ -10,15 +10,30 @@
 // 256 accumulator registers of dK^T and dV^T live in the accumulation half of the register file
 // (they are only ever touched by products, issued from inline asm with an "a" constraint: the compiler
 // cannot be told to keep a builtin product's accumulator there), and everything a vector instruction
-// reads stays in the 256 architectural registers.  With no second wave on the SIMD, the wave overlaps
-// its own work: an iteration runs the score products of step t+1 (S, dP: 32 products, LDS row reads),
-// then the 32 gradient products of step t with the element-wise work of step t+1 (exp2, dS, packing)
-// spread between them, one value after each product.  Query steps are 32 rows; their Q/dO tiles are
-// staged two steps ahead through three LDS stages; the block's 256 V rows stay in LDS.
+// reads stays in the 256 architectural registers.
 //
-// Hazards of the inline-asm products: their results are read only by later products on the same
-// accumulator (at least three other products in between) and, after the loop, behind explicit
-// wait states; their B operands were packed by vector instructions a whole phase earlier.
+// With no second wave on the SIMD, a wave overlaps its own work, and the unit of overlap is the slot
+// behind a product: the matrix unit is busy for 32 cycles per product, a product takes 4 cycles to
+// issue, so about 28 cycles of other instructions (4 cycles each, an LDS read or a transcendental
+// more) fit behind it for free, and whatever exceeds that, or is issued with no product running,
+// costs its full time.  An iteration therefore runs
+//   - 4 products that start the score accumulators S, dP of step t+1 at minus the row statistics
+//     (the statistics come from the delta kernel as bf16 triples, one 16-byte load per lane and step),
+//   - the 32 score products of step t+1, with one LDS row read (for two head-dim steps ahead) and one
+//     piece of bookkeeping behind each: the walk to step t+2, the loads that stage its Q/dO tiles and
+//     statistics, its masks, the moves of the fragment addresses to the next LDS stage, the first
+//     transposed reads of the gradient phase,
+//   - the 32 gradient products of step t, with one transposed LDS read and one slot of the element-
+//     wise work of step t+1 (exp2, dS, packing to bf16) behind each,
+//   - one barrier.
+// Query steps are 32 rows; their tiles are staged two steps ahead through three LDS stages; the
+// block's 256 V rows stay in LDS, its K fragments in registers.
+//
+// Hazards of the inline-asm products (the compiler does not know what they are and adds no wait
+// states): their results are read only by later products on the same accumulator (at least three
+// other products in between) and, after the loop or in the masked path, behind explicit wait states;
+// their B operands were packed by vector instructions a whole phase earlier, except the zero
+// fragments of the first step (see mfma_acc).
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -102,10 +117,6 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v
       }
     }
   }
-#ifdef DK128_TIMING
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(s[0]), "+v"(s[1]), "+v"(dp[0]), "+v"(dp[1]));
-  between(IC<100>{});
-#endif
   static_for<0, kNKS>([&](auto uc) {
     constexpr int u = decltype(uc)::value;
     constexpr bool more = u + 2 < kNKS;
@@ -252,21 +263,21 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   int lo = max(sg.q_lo, it.kv_row0);
   int n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
   bool more = true;                                     // the walk has a step that was not handed out yet
-  auto next_step = [&](Step& d) -> bool {
+  auto next_step = [&](Step& d) -> bool {              // straight-line in the common case (same run, next head or step)
     if (!more) return false;
     d.i0 = lo + n * kQStep;
     d.hi = sg.q_hi;
     d.head = hk * g + hh;
-    if (++hh == g) {
-      hh = 0;
-      if (--n < 0) {
-        if (--sgi < it.seg_begin) {
-          more = false;
-        } else {
-          sg = segs[sgi];
-          lo = max(sg.q_lo, it.kv_row0);
-          n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
-        }
+    const bool wrap = hh + 1 == g;
+    hh = wrap ? 0 : hh + 1;
+    n -= wrap ? 1 : 0;
+    if (__builtin_expect(n < 0, 0)) {                   // the run is used up: the one before it, if any
+      if (--sgi < it.seg_begin) {
+        more = false;
+      } else {
+        sg = segs[sgi];
+        lo = max(sg.q_lo, it.kv_row0);
+        n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
       }
     }
     return true;
@@ -339,7 +350,7 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   // has no d_s: scores and element-wise work run on the stale tile of stage st_s and nobody uses them.
   // Stage st_n's last readers (the gradient products two iterations back) finished before the barrier
   // that ended the previous iteration.
-  uintx4 pf[2][2], ds[2][2];
+  uintx4 pf[2][2], ds[2][2];                            // packed P, dS of the step whose gradient products come next
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -347,14 +358,6 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   int st_s = 0;
   int dt_pend = 0;                                      // pqt's move to the stage scored last, applied in the next score phase
   bool again;
-#ifdef DK128_TIMING
-  auto stamp = [] { unsigned long long t; asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)); return (long long)t; };
-  long long tacc[5] = {0, 0, 0, 0, 0}, tprev = stamp(), tbegin = tprev, wbegin = wall_clock64();
-  int n_it = 0;
-#define DK128_STAMP(i) { const long long t_ = stamp(); tacc[i] += t_ - tprev; tprev = t_; }
-#else
-#define DK128_STAMP(i)
-#endif
   auto iteration = [&](auto first_c) {
     constexpr bool first = decltype(first_c)::value != 0;
     const int st_n = st_s == 2 ? 0 : st_s + 1;
@@ -365,9 +368,6 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     const int m0_n = st_n * kStageBytes + wave_off;     // where this wave's lines of the first pass go
     auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
       constexpr int k = decltype(kc)::value;
-#ifdef DK128_TIMING
-      if constexpr (k == 100) DK128_STAMP(4)
-#endif
       if constexpr (k < 4) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
       if constexpr (k == 4) have_n = have_s && next_step(d_n);
       if constexpr (k == 6) stat_n = load_stat(d_n);      // d_n always names a real step (the last one, when the walk has ended)
@@ -377,9 +377,9 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
       }
       if constexpr (k >= 9 && k < 13) {                  // one load each: [Q pass 0, Q pass 1, dO pass 0, dO pass 1]
         constexpr int tile = (k - 9) >> 1, pass = (k - 9) & 1;
-        if (have_n)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes + pass * 4096, 16,
-                                                   voff_n, soff_n + pass * 16 * srcQ.row_bytes, 0, 0);
+        // (when the walk has ended d_n still names the last step: its tile is staged once more, into a stage nobody reads)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes + pass * 4096, 16,
+                                                 voff_n, soff_n + pass * 16 * srcQ.row_bytes, 0, 0);
       }
       if constexpr (k == 13) m_n = masks(d_n);
       if constexpr (k >= 24 && k < 32) {                 // the gradient phase's first two batches of reads
@@ -388,21 +388,17 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
       }
       if constexpr (k == 31) v_rel -= dq_;
     };
-    DK128_STAMP(0)
     floatx16 s[2], dp[2];
     uintx4 npf[2][2], nds[2][2];
     const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
     score_products(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, m_s.rel_hi, between);
-    DK128_STAMP(1)
     gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) { pf[kb][h2] = npf[kb][h2]; ds[kb][h2] = nds[kb][h2]; }
-    DK128_STAMP(2)
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    DK128_STAMP(3)
     again = have_s;
     d_s = d_n;
     m_s = m_n;
@@ -415,19 +411,7 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     if (!again) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
   };
   iteration(IC<1>{});
-  while (again) {
-    iteration(IC<0>{});
-#ifdef DK128_TIMING
-    ++n_it;
-#endif
-  }
-#ifdef DK128_TIMING
-  if (tid == 0) {   // timing build: one record per block at the start of the (otherwise unused) fp32 accumulators
-    long long* rec = reinterpret_cast<long long*>(acc_dk) + 10 * (size_t)blockIdx.x;
-    rec[0] = n_it; rec[1] = stamp() - tbegin; rec[2] = wbegin; rec[3] = wall_clock64();
-    rec[4] = tacc[0]; rec[5] = tacc[4]; rec[6] = tacc[1]; rec[7] = tacc[2]; rec[8] = tacc[3]; rec[9] = 1;
-  }
-#endif
+  while (again) iteration(IC<0>{});
 
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
