@@ -75,14 +75,15 @@ __device__ __forceinline__ void mfma_acc(floatx16& acc, bf16x8 a, bf16x8 b) {
 // product with a fragment of ones (ones_l picks the first triple, ones_d the second; zero in the upper
 // half-wave, whose copy of `stat` therefore does not count) puts their sums into every column of the
 // row.  That costs four products and no vector or LDS instruction, where loading the 64 accumulator
-// registers costs a quarter of the phase.  In `masked` steps the scores of pairs that do not count
-// (local row - 4*half outside [rel_lo[kb], rel_hi): before the lane's key, or past the end of the query
-// run) are then set to -inf, so that their probability and dS come out as zero.  One batch of LDS
-// reads per head-dim step: the Q and dO fragments and the two V fragments.
+// registers costs a quarter of the phase.  A row past the end of its query run comes with -2^100 in
+// place of -lse2 (and 0 for -delta; the caller's doing): its probabilities and dS are zero.  In
+// `masked` steps (the step's rows reach back to or before the wave's last key) the scores of rows
+// before the lane's key (local row - 4*half < rel_lo[kb]) are then set to -inf, with the same effect.
+// One batch of LDS reads per head-dim step: the Q and dO fragments and the two V fragments.
 template <class Between>
 __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v_rel, bf16x8 stat, uintx4 ones_l, uintx4 ones_d,
                                                const bf16x8 (&kf)[2][kNKS], floatx16 (&s)[2], floatx16 (&dp)[2],
-                                               bool masked, const int (&rel_lo)[2], int rel_hi, Between&& between) {
+                                               bool masked, const int (&rel_lo)[2], Between&& between) {
   // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
   // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
   // issue time of a plain instruction: four in a row would outlast the product they follow); those of
@@ -108,14 +109,12 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v
     // their results by the wait states the hardware needs
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const unsigned span = (unsigned)max(rel_hi - rel_lo[kb], 0);   // c - rel_lo in [0, span) <=> the pair counts
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int c = 8 * (r >> 2) + (r & 3);           // c + 4*half = local row
-        s[kb][r] = (unsigned)(c - rel_lo[kb]) < span ? s[kb][r] : -INFINITY;
+        s[kb][r] = c >= rel_lo[kb] ? s[kb][r] : -INFINITY;
       }
-    }
   }
   static_for<0, kNKS>([&](auto uc) {
     constexpr int u = decltype(uc)::value;
@@ -292,7 +291,7 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     stage_tile<kD, kQStep, 256>(lds + st * kStageBytes, a, d.i0 - it.kv_row0, tid);
     stage_tile<kD, kQStep, 256>(lds + st * kStageBytes + kTileBytes, b, d.i0 - it.kv_row0, tid);
   };
-  // a step's statistics for this lane's row: -lse2, -delta as bf16 triples (rows past the end are masked)
+  // a step's statistics for this lane's row: -lse2, -delta as bf16 triples (rows past the end of the run: see the loop)
   auto load_stat = [&](const Step& d) -> bf16x8 { return stat3[(size_t)d.head * T + min(d.i0 + l32, T - 1)]; };
 
   Step d_s, d_n;                                        // the step whose scores come next, the step to stage
@@ -330,12 +329,11 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  // masks of a step for this wave: local rows [rel_lo0 (+32 for the second key block), rel_hi) minus
-  // 4*half contribute; `masked` (wave-uniform): some row of the step is masked
-  struct Mask { int rel_lo0, rel_hi; bool masked; };
-  auto masks = [&](const Step& d) -> Mask {
-    return Mask{kv0w + l32 - d.i0 - 4 * half, d.hi - d.i0 - 4 * half, !(d.i0 >= kv0w + 63 && d.i0 + kQStep <= d.hi)};
-  };
+  // Masks of a step for this wave.  Causal: local rows >= rel_lo0 (+32 for the second key block) + 4*half
+  // count; `masked` (wave-uniform): the step has a row before the wave's last key.  End of the query run:
+  // the step's first `rows` rows exist (wave-uniform; < 32 only in a run's last step).
+  struct Mask { int rel_lo0, rows; bool masked; };
+  auto masks = [&](const Step& d) -> Mask { return Mask{kv0w + l32 - d.i0 - 4 * half, d.hi - d.i0, d.i0 < kv0w + 63}; };
   Mask m_s = masks(d_s), m_n = m_s;
   const int wave_off = __builtin_amdgcn_readfirstlane((tid >> 6) * 1024);   // this wave's lines within a staging pass
 
@@ -391,7 +389,14 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     floatx16 s[2], dp[2];
     uintx4 npf[2][2], nds[2][2];
     const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
-    score_products(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, m_s.rel_hi, between);
+    if (m_s.rows < kQStep) {
+      // a run's last step: rows past its end get -2^100 in place of -lse2 and 0 for -delta, so their
+      // probabilities and dS come out as zero (the wait states: a vector write right before an asm product)
+      const bf16x8 gone = __builtin_bit_cast(bf16x8, uintx4{0x0000F180u, 0u, 0u, 0u});
+      stat_s = l32 < m_s.rows ? stat_s : gone;
+      asm volatile("s_nop 7" : "+v"(stat_s));
+    }
+    score_products(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, between);
     gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)

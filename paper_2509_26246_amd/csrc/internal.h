@@ -37,7 +37,9 @@ struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts; };
 // fewer blocks share the work and the more a single long sample's first tiles dominate the makespan.
 constexpr int kNumSplitTiles = 2;
 constexpr int kSplitTileRows[kNumSplitTiles] = {128, 256};
-constexpr int kSplitBlockSlots[kNumSplitTiles] = {512, 256};   // resident blocks of the kernel that uses the tile
+constexpr int kSplitBlockSlots[kNumSplitTiles] = {512, 192};   // slots the per-slot share is taken over: the 128-key kernel's
+                                                                // resident blocks; 3/4 of the 256-key kernel's (measured: its
+                                                                // parts cost more to set up, so it divides less)
 inline int split_tile_index(int rows) { return rows == 128 ? 0 : rows == 256 ? 1 : -1; }
 constexpr int kNumSplitClasses = 4;
 inline int split_class(int n_kv_heads) { return n_kv_heads >= 8 ? 3 : n_kv_heads >= 4 ? 2 : n_kv_heads >= 2 ? 1 : 0; }
