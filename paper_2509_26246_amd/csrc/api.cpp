@@ -123,7 +123,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
     rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
       return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
-                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2, use_dkdv128(p->dtype, p->head_dim) ? stat3 : nullptr);
+                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2, use_dkdv_wide(p->dtype, p->head_dim) ? stat3 : nullptr);
     }));
     if (rc != SLIMATTN_OK) return rc;
   }
@@ -141,8 +141,8 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
       return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
                                        delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
                                        store_final)
-                 : use_dkdv128(p->dtype, p->head_dim)
-                     ? launch_bwd_dkdv128_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
+                 : use_dkdv_wide(p->dtype, p->head_dim)
+                     ? launch_bwd_dkdv_wide_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
                                                store_final, parts)
                      : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
                                             store_final, parts);

@@ -532,7 +532,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 }  // namespace
 
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
-int dkdv_kv_tile(int dtype, int head_dim) { return dtype == SLIMATTN_F32 ? 64 : use_dkdv128(dtype, head_dim) ? 256 : kKvOwn; }
+int dkdv_kv_tile(int dtype, int head_dim) { return dtype == SLIMATTN_F32 ? 64 : use_dkdv_wide(dtype, head_dim) ? 256 : kKvOwn; }
 
 int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2,
                           void* stat3) {

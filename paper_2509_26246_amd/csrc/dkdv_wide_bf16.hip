@@ -1,13 +1,13 @@
-// dK/dV at head_dim 128, bf16 inputs: one wave per SIMD, 64 key rows per wave.
+// dK/dV for bf16 inputs at head dim 128 or 64: 256 key rows per block, one wave per SIMD, 64 key rows per wave.
 //
 // What it computes is the dK/dV step of the backward (see bwd_bf16.hip): a block owns key rows of one
 // KV head and walks every query row of the launch scope at or after them, for every query head of the
 // group, in a fixed order; S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.
 //
-// Shape on CDNA4.  The kernel that keeps two waves per SIMD (32 keys per wave) is at its register
-// limit and reads 1.25 KB of LDS per product.  Here a block is 4 waves, one per SIMD, and a wave owns
+// Shape on CDNA4.  A kernel that keeps two waves per SIMD (32 keys per wave, 128 per block) is at its
+// register limit at head dim 128 and reads 1.25 KB of LDS per product.  Here a block is 4 waves, one per SIMD, and a wave owns
 // 64 keys (two 32-key blocks): every Q, dO, Q^T and dO^T fragment read from LDS feeds two products, the
-// 256 accumulator registers of dK^T and dV^T live in the accumulation half of the register file
+// accumulator registers of dK^T and dV^T (256 at head dim 128) live in the accumulation half of the register file
 // (they are only ever touched by products, issued from inline asm with an "a" constraint: the compiler
 // cannot be told to keep a builtin product's accumulator there), and everything a vector instruction
 // reads stays in the 256 architectural registers.
@@ -42,14 +42,17 @@
 namespace slimattn {
 namespace {
 
-constexpr int kD = 128, kNKS = kD / 16, kNDB = kD / 32, kRowBytes = kD * 2;
 constexpr int kKeys = 256;                              // key rows per block: 4 waves x 64
 constexpr int kQStep = 32;
-constexpr int kTileBytes = kQStep * kRowBytes;          // one Q or dO tile
-constexpr int kStageBytes = 2 * kTileBytes;             // [Q tile, dO tile]
 constexpr int kStages = 3;
-constexpr int kVBase = kStages * kStageBytes;
-constexpr int kVBytes = kKeys * kRowBytes;
+template <int D> constexpr int kNKS = D / 16;           // head-dim steps of a score product
+template <int D> constexpr int kNDB = D / 32;           // head-dim blocks of a gradient accumulator
+template <int D> constexpr int kRowBytes = D * 2;
+template <int D> constexpr int kTileBytes = kQStep * kRowBytes<D>;   // one Q or dO tile
+template <int D> constexpr int kStageBytes = 2 * kTileBytes<D>;      // [Q tile, dO tile]
+template <int D> constexpr int kVBase = kStages * kStageBytes<D>;
+template <int D> constexpr int kVBytes = kKeys * kRowBytes<D>;
+template <int D> constexpr int kGradBatches = 2 * kNDB<D>;           // batches of transposed reads in the gradient phase
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uintx4;   // a packed bf16x8 fragment, by dword
@@ -80,22 +83,22 @@ __device__ __forceinline__ void mfma_acc(floatx16& acc, bf16x8 a, bf16x8 b) {
 // `masked` steps (the step's rows reach back to or before the wave's last key) the scores of rows
 // before the lane's key (local row - 4*half < rel_lo[kb]) are then set to -inf, with the same effect.
 // One batch of LDS reads per head-dim step: the Q and dO fragments and the two V fragments.
-template <class Between>
-__device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v_rel, bf16x8 stat, uintx4 ones_l, uintx4 ones_d,
-                                               const bf16x8 (&kf)[2][kNKS], floatx16 (&s)[2], floatx16 (&dp)[2],
+template <int D, class Between>
+__device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS<D>], int v_rel, bf16x8 stat, uintx4 ones_l, uintx4 ones_d,
+                                               const bf16x8 (&kf)[2][kNKS<D>], floatx16 (&s)[2], floatx16 (&dp)[2],
                                                bool masked, const int (&rel_lo)[2], Between&& between) {
   // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
   // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
   // issue time of a plain instruction: four in a row would outlast the product they follow); those of
   // the first two steps run while the accumulators are started.
-  R4 g[kNKS];
+  R4 g[kNKS<D>];
   lds_cptr pv = pq[0];
   auto issue_one = [&](auto uc, auto ic) {
     constexpr int u = decltype(uc)::value, i = decltype(ic)::value;
     if constexpr (i == 0) r1_issue<0>(pq[u], g[u].f[0]);
-    if constexpr (i == 1) { r1_issue<kTileBytes>(pq[u], g[u].f[1]); pv = pq[u] + v_rel; }
+    if constexpr (i == 1) { r1_issue<kTileBytes<D>>(pq[u], g[u].f[1]); pv = pq[u] + v_rel; }
     if constexpr (i == 2) r1_issue<0>(pv, g[u].f[2]);
-    if constexpr (i == 3) r1_issue<32 * kRowBytes>(pv, g[u].f[3]);
+    if constexpr (i == 3) r1_issue<32 * kRowBytes<D>>(pv, g[u].f[3]);
   };
   static_for<0, 4>([&](auto ic) { issue_one(IC<0>{}, ic); });
   // asm: two of the four products are equal and the compiler would compute them once and copy
@@ -116,9 +119,9 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS], int v
         s[kb][r] = c >= rel_lo[kb] ? s[kb][r] : -INFINITY;
       }
   }
-  static_for<0, kNKS>([&](auto uc) {
+  static_for<0, kNKS<D>>([&](auto uc) {
     constexpr int u = decltype(uc)::value;
-    constexpr bool more = u + 2 < kNKS;
+    constexpr bool more = u + 2 < kNKS<D>;
     lds_wait<4>(g[u]);                                  // behind step u: step u + 1 or, at the end, a batch of gradient reads
     s[0] = mfma32(g[u].f[0], kf[0][u], s[0]);
     if constexpr (more) issue_one(IC<u + 2>{}, IC<0>{});
@@ -186,11 +189,10 @@ __device__ __forceinline__ void ew_slot(floatx16 (&s)[2], floatx16 (&dp)[2], uin
 
 // Read i (of four) of gradient batch B: the dO^T fragment (reads 0, 1) and the Q^T fragment (2, 3) of
 // head-dim block B % 4, rows 16 (B / 4) .. +16 of the step's tiles.
-constexpr int kGradBatches = 2 * kNDB;
-template <int B, int I>
-__device__ __forceinline__ void grad_read(const lds_cptr (&pqt)[kNDB][2], Tr2 (&tb)[kGradBatches]) {
-  constexpr int st = B / kNDB, db = B % kNDB;
-  tr1_issue<st * 16 * kRowBytes + (I < 2 ? kTileBytes : 0)>(pqt[db][I & 1], tb[B].r[I]);
+template <int D, int B, int I>
+__device__ __forceinline__ void grad_read(const lds_cptr (&pqt)[kNDB<D>][2], Tr2 (&tb)[kGradBatches<D>]) {
+  constexpr int st = B / kNDB<D>, db = B % kNDB<D>;
+  tr1_issue<st * 16 * kRowBytes<D> + (I < 2 ? kTileBytes<D> : 0)>(pqt[db][I & 1], tb[B].r[I]);
 }
 
 // Gradient products of one step, dV_kb^T += dO^T P_kb and dK_kb^T += Q^T dS_kb, with P, dS packed in
@@ -198,34 +200,39 @@ __device__ __forceinline__ void grad_read(const lds_cptr (&pqt)[kNDB][2], Tr2 (&
 // one batch of two transposed fragments (dO^T, Q^T), each feeding both key blocks.  The element-wise work
 // of the next step (its scores in s, dp) is spread between the products, one value after each, and its
 // packed results are left in npf, nds.  FIRST: the block's first call, which starts the accumulators.
-template <bool FIRST>
-__device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB][2], const uintx4 (&pf)[2][2],
-                                                  const uintx4 (&ds)[2][2], floatx16 (&dk)[2][kNDB], floatx16 (&dv)[2][kNDB],
+template <int D, bool FIRST>
+__device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB<D>][2], const uintx4 (&pf)[2][2],
+                                                  const uintx4 (&ds)[2][2], floatx16 (&dk)[2][kNDB<D>], floatx16 (&dv)[2][kNDB<D>],
                                                   floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2],
-                                                  uintx4 (&nds)[2][2], Tr2 (&tb)[kGradBatches]) {
+                                                  uintx4 (&nds)[2][2], Tr2 (&tb)[kGradBatches<D>]) {
   // batch b: head-dim block b % 4 of 16-row half b / 4 (first half first: its P, dS die early); its
   // four reads are issued one behind each product of batch b - 2, those of batches 0 and 1 behind the
   // last score products (by the caller)
-  static_for<0, kGradBatches>([&](auto ic) {
-    constexpr int b = decltype(ic)::value, st = b / kNDB, db = b % kNDB;
-    constexpr bool more = b + 2 < kGradBatches;
-    lds_wait<(b + 1 < kGradBatches) ? 4 : 0>(tb[b]);
+  constexpr int kPer = 32 / (4 * kGradBatches<D>);       // element-wise values per product slot (1 at d 128, 2 at d 64)
+  auto ew = [&](auto qc) {                              // the element-wise work behind product q of the phase
+    constexpr int q = decltype(qc)::value;
+    static_for<0, kPer>([&](auto ec) { ew_slot<kPer * q + decltype(ec)::value>(s, dp, npf, nds); });
+  };
+  static_for<0, kGradBatches<D>>([&](auto ic) {
+    constexpr int b = decltype(ic)::value, st = b / kNDB<D>, db = b % kNDB<D>;
+    constexpr bool more = b + 2 < kGradBatches<D>;
+    lds_wait<(b + 1 < kGradBatches<D>) ? 4 : 0>(tb[b]);
     constexpr bool kStart = FIRST && st == 0;
     mfma_acc<kStart>(dv[0][db], tr2_frag(tb[b], 0), as_frag(pf[0][st]));
-    if constexpr (more) grad_read<b + 2, 0>(pqt, tb);
-    ew_slot<4 * b + 0>(s, dp, npf, nds);
+    if constexpr (more) grad_read<D, b + 2, 0>(pqt, tb);
+    ew(IC<4 * b + 0>{});
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dv[1][db], tr2_frag(tb[b], 0), as_frag(pf[1][st]));
-    if constexpr (more) grad_read<b + 2, 1>(pqt, tb);
-    ew_slot<4 * b + 1>(s, dp, npf, nds);
+    if constexpr (more) grad_read<D, b + 2, 1>(pqt, tb);
+    ew(IC<4 * b + 1>{});
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dk[0][db], tr2_frag(tb[b], 1), as_frag(ds[0][st]));
-    if constexpr (more) grad_read<b + 2, 2>(pqt, tb);
-    ew_slot<4 * b + 2>(s, dp, npf, nds);
+    if constexpr (more) grad_read<D, b + 2, 2>(pqt, tb);
+    ew(IC<4 * b + 2>{});
     __builtin_amdgcn_sched_barrier(0);
     mfma_acc<kStart>(dk[1][db], tr2_frag(tb[b], 1), as_frag(ds[1][st]));
-    if constexpr (more) grad_read<b + 2, 3>(pqt, tb);
-    ew_slot<4 * b + 3>(s, dp, npf, nds);
+    if constexpr (more) grad_read<D, b + 2, 3>(pqt, tb);
+    ew(IC<4 * b + 3>{});
     __builtin_amdgcn_sched_barrier(0);
   });
 }
@@ -240,12 +247,13 @@ __device__ __forceinline__ void lds_ptr_add(lds_cptr& p, int d) {
 
 struct Step { int i0, hi, head; };                      // rows [i0, min(i0 + 32, hi)) of one query head
 
-__global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
+template <int D>
+__device__ __forceinline__ void dkdv_wide_block(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
     int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
-  __shared__ __attribute__((aligned(1024))) char smem[kVBase + kVBytes];   // three [Q, dO] stages, then the V tile
+  __shared__ __attribute__((aligned(1024))) char smem[kVBase<D> + kVBytes<D>];   // three [Q, dO] stages, then the V tile
 
   const int g = Hq / Hkv;
   const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
@@ -282,14 +290,14 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     return true;
   };
 
-  const TileSource srcQ = make_tile_source<kD, 256>(q, it.kv_row0, Hq, 0, T, tid);
-  const TileSource srcDO = make_tile_source<kD, 256>(dO, it.kv_row0, Hq, 0, T, tid);
+  const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
+  const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
   auto stage = [&](const Step& d, int st) {             // a step's Q and dO tiles straight into LDS
     TileSource a = srcQ, b = srcDO;
-    a.voff += d.head * kRowBytes;
-    b.voff += d.head * kRowBytes;
-    stage_tile<kD, kQStep, 256>(lds + st * kStageBytes, a, d.i0 - it.kv_row0, tid);
-    stage_tile<kD, kQStep, 256>(lds + st * kStageBytes + kTileBytes, b, d.i0 - it.kv_row0, tid);
+    a.voff += d.head * kRowBytes<D>;
+    b.voff += d.head * kRowBytes<D>;
+    stage_tile<D, kQStep, 256>(lds + st * kStageBytes<D>, a, d.i0 - it.kv_row0, tid);
+    stage_tile<D, kQStep, 256>(lds + st * kStageBytes<D> + kTileBytes<D>, b, d.i0 - it.kv_row0, tid);
   };
   // a step's statistics for this lane's row: -lse2, -delta as bf16 triples (rows past the end of the run: see the loop)
   auto load_stat = [&](const Step& d) -> bf16x8 { return stat3[(size_t)d.head * T + min(d.i0 + l32, T - 1)]; };
@@ -303,15 +311,15 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   const uintx4 ones_l = {one2, one1, 0u, 0u}, ones_d = {0u, 0u, one2, one1};
   bool have_s = true;
   {
-    const TileSource srcV = make_tile_source<kD, 256>(v, it.kv_row0, Hkv, hk, T, tid);
-    stage_tile<kD, kKeys, 256>(lds + kVBase, srcV, 0, tid);
+    const TileSource srcV = make_tile_source<D, 256>(v, it.kv_row0, Hkv, hk, T, tid);
+    stage_tile<D, kKeys, 256>(lds + kVBase<D>, srcV, 0, tid);
   }
-  bf16x8 kf[2][kNKS];
+  bf16x8 kf[2][kNKS<D>];
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
-    const size_t off = ((size_t)min(kv0w + 32 * kb + l32, T - 1) * Hkv + hk) * kD + 8 * half;
+    const size_t off = ((size_t)min(kv0w + 32 * kb + l32, T - 1) * Hkv + hk) * D + 8 * half;
 #pragma unroll
-    for (int ks = 0; ks < kNKS; ++ks) {
+    for (int ks = 0; ks < kNKS<D>; ++ks) {
       kf[kb][ks] = scale8(*reinterpret_cast<const bf16x8*>(k + off + 16 * ks), scale * kLog2e);
       __builtin_amdgcn_sched_barrier(0);              // one fragment at a time: this set-up code must not need many registers
     }
@@ -319,13 +327,13 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   // pq[]: row-fragment addresses in the stage of the step whose scores are computed next; pqt[][]:
   // transposed-fragment addresses in the stage of the step whose gradients are computed next.  Both move
   // one stage per iteration (with wrap-around), so every LDS offset in the products is an immediate.
-  lds_cptr pq[kNKS], pqt[kNDB][2];
+  lds_cptr pq[kNKS<D>], pqt[kNDB<D>][2];
 #pragma unroll
-  for (int ks = 0; ks < kNKS; ++ks) pq[ks] = lds_row_ptr<kD>(lds, l32, 16 * ks + 8 * half);
+  for (int ks = 0; ks < kNKS<D>; ++ks) pq[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
 #pragma unroll
-  for (int db = 0; db < kNDB; ++db) lds_tr_ptrs<kD>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
-  int v_rel = kVBase + wave * 64 * kRowBytes;           // the swizzle of row 64 w + 32 kb + l32 equals that of row l32
-  floatx16 dk[2][kNDB], dv[2][kNDB];                    // started by the first iteration's products
+  for (int db = 0; db < kNDB<D>; ++db) lds_tr_ptrs<D>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
+  int v_rel = kVBase<D> + wave * 64 * kRowBytes<D>;           // the swizzle of row 64 w + 32 kb + l32 equals that of row l32
+  floatx16 dk[2][kNDB<D>], dv[2][kNDB<D>];                    // started by the first iteration's products
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
@@ -359,32 +367,37 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   auto iteration = [&](auto first_c) {
     constexpr bool first = decltype(first_c)::value != 0;
     const int st_n = st_s == 2 ? 0 : st_s + 1;
-    const int dq_ = st_s == 2 ? -2 * kStageBytes : kStageBytes;   // pq's move to the next stage
+    const int dq_ = st_s == 2 ? -2 * kStageBytes<D> : kStageBytes<D>;   // pq's move to the next stage
     bool have_n = false;
     int voff_n = 0, soff_n = 0;
-    Tr2 tb[kGradBatches];                               // the gradient phase's batches of transposed fragments
-    const int m0_n = st_n * kStageBytes + wave_off;     // where this wave's lines of the first pass go
+    Tr2 tb[kGradBatches<D>];                               // the gradient phase's batches of transposed fragments
+    const int m0_n = st_n * kStageBytes<D> + wave_off;     // where this wave's lines of the first pass go
+    // slots of the pieces (behind score product k): spread out at d 128 (32 slots), packed at d 64 (16)
+    constexpr int kSlotNext = D == 128 ? 4 : 2, kSlotStat = D == 128 ? 6 : 3, kSlotAddr = D == 128 ? 8 : 4;
+    constexpr int kSlotLoad = D == 128 ? 9 : 5, kSlotMask = D == 128 ? 13 : 7, kSlotGrad = 4 * (kNKS<D> - 2);
+    constexpr int kPasses = kTileBytes<D> / 4096;         // staging loads per tile (256 threads x 16 bytes each)
     auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
       constexpr int k = decltype(kc)::value;
-      if constexpr (k < 4) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
-      if constexpr (k == 4) have_n = have_s && next_step(d_n);
-      if constexpr (k == 6) stat_n = load_stat(d_n);      // d_n always names a real step (the last one, when the walk has ended)
-      if constexpr (k == 8) {
-        voff_n = srcQ.voff + d_n.head * kRowBytes;      // the Q and dO sources differ in their descriptors only
+      if constexpr (k < kNDB<D>) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
+      if constexpr (k == kSlotNext) have_n = have_s && next_step(d_n);
+      if constexpr (k == kSlotStat) stat_n = load_stat(d_n);   // d_n always names a real step (the last one, when the walk has ended)
+      if constexpr (k == kSlotAddr) {
+        voff_n = srcQ.voff + d_n.head * kRowBytes<D>;   // the Q and dO sources differ in their descriptors only
         soff_n = (d_n.i0 - it.kv_row0) * srcQ.row_bytes;
       }
-      if constexpr (k >= 9 && k < 13) {                  // one load each: [Q pass 0, Q pass 1, dO pass 0, dO pass 1]
-        constexpr int tile = (k - 9) >> 1, pass = (k - 9) & 1;
+      if constexpr (k >= kSlotLoad && k < kSlotLoad + 2 * kPasses) {   // one load each: the passes of the Q tile, then of the dO tile
+        constexpr int tile = (k - kSlotLoad) / kPasses, pass = (k - kSlotLoad) % kPasses;
+        constexpr int kRowsPerPass = 4096 / kRowBytes<D>;
         // (when the walk has ended d_n still names the last step: its tile is staged once more, into a stage nobody reads)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes + pass * 4096, 16,
-                                                 voff_n, soff_n + pass * 16 * srcQ.row_bytes, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes<D> + pass * 4096, 16,
+                                                 voff_n, soff_n + pass * kRowsPerPass * srcQ.row_bytes, 0, 0);
       }
-      if constexpr (k == 13) m_n = masks(d_n);
-      if constexpr (k >= 24 && k < 32) {                 // the gradient phase's first two batches of reads
-        grad_read<(k - 24) / 4, (k - 24) % 4>(pqt, tb);
-        lds_ptr_add(pq[k - 24], dq_);
+      if constexpr (k == kSlotMask) m_n = masks(d_n);
+      if constexpr (k >= kSlotGrad && k < kSlotGrad + 8) {   // the gradient phase's first two batches of reads
+        grad_read<D, (k - kSlotGrad) / 4, (k - kSlotGrad) % 4>(pqt, tb);
+        if constexpr (k - kSlotGrad < kNKS<D>) lds_ptr_add(pq[k - kSlotGrad], dq_);
       }
-      if constexpr (k == 31) v_rel -= dq_;
+      if constexpr (k == kSlotGrad + 7) v_rel -= dq_;
     };
     floatx16 s[2], dp[2];
     uintx4 npf[2][2], nds[2][2];
@@ -396,8 +409,8 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
       stat_s = l32 < m_s.rows ? stat_s : gone;
       asm volatile("s_nop 7" : "+v"(stat_s));
     }
-    score_products(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, between);
-    gradient_products<first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
+    score_products<D>(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, between);
+    gradient_products<D, first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -409,7 +422,7 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     m_s = m_n;
     stat_s = stat_n;
     have_s = have_n;
-    dt_pend = first ? 0 : (st_s == 0 ? -2 * kStageBytes : kStageBytes);   // pqt moves to the stage just scored
+    dt_pend = first ? 0 : (st_s == 0 ? -2 * kStageBytes<D> : kStageBytes<D>);   // pqt moves to the stage just scored
     st_s = st_n;
     // the last products' results must have landed before any vector instruction reads them (the
     // compiler does not know that the asm statements are matrix products): explicit wait states
@@ -423,10 +436,10 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
     const int my_key = kv0w + 32 * kb + l32;
     if (it.slot >= 0) {
       // one part of a divided key tile: fp32 partial tile [slot][kv head][dK, dV][256 rows][D]
-      float* pk_ = parts + ((size_t)it.slot * Hkv + hk) * (2 * kKeys * kD) + (size_t)(64 * wave + 32 * kb + l32) * kD;
-      float* pv_ = pk_ + kKeys * kD;
+      float* pk_ = parts + ((size_t)it.slot * Hkv + hk) * (2 * kKeys * D) + (size_t)(64 * wave + 32 * kb + l32) * D;
+      float* pv_ = pk_ + kKeys * D;
 #pragma unroll
-      for (int db = 0; db < kNDB; ++db)
+      for (int db = 0; db < kNDB<D>; ++db)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           const int off = 32 * db + 8 * gq + 4 * half;
@@ -437,9 +450,9 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
           *reinterpret_cast<floatx4*>(pv_ + off) = b;
         }
     } else if (my_key < kv_end) {
-      const size_t base = ((size_t)my_key * Hkv + hk) * kD;
+      const size_t base = ((size_t)my_key * Hkv + hk) * D;
 #pragma unroll
-      for (int db = 0; db < kNDB; ++db)
+      for (int db = 0; db < kNDB<D>; ++db)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           const size_t off = base + 32 * db + 8 * gq + 4 * half;
@@ -465,17 +478,38 @@ __global__ __launch_bounds__(256, 1) void dkdv128_bf16_kernel(
   }
 }
 
+// One kernel per head dim (plain functions: the launch below names them).
+__global__ __launch_bounds__(256, 1) void dkdv_wide_bf16_kernel_d128(
+    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
+    const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv, bf16* __restrict__ dK,
+    bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs, int T, int Hq, int Hkv,
+    float scale, int load_acc, int store_final, float* __restrict__ parts) {
+  dkdv_wide_block<128>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, load_acc, store_final, parts);
+}
+__global__ __launch_bounds__(256, 1) void dkdv_wide_bf16_kernel_d64(
+    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
+    const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv, bf16* __restrict__ dK,
+    bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs, int T, int Hq, int Hkv,
+    float scale, int load_acc, int store_final, float* __restrict__ parts) {
+  dkdv_wide_block<64>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, load_acc, store_final, parts);
+}
+
 }  // namespace
 
-int launch_bwd_dkdv128_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
-                            float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                            int n_items, const Seg* segs, int load_acc, int store_final, float* parts) {
+int launch_bwd_dkdv_wide_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
+                            float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
+                            int load_acc, int store_final, float* parts) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
-  hipLaunchKernelGGL(dkdv128_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                     (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items, segs,
-                     (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(dkdv_wide_bf16_kernel_d128, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+  else
+    hipLaunchKernelGGL(dkdv_wide_bf16_kernel_d64, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
   return (int)hipGetLastError();
 }
 

@@ -114,8 +114,8 @@ int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const voi
 int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                          const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
                          int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
-// head_dim 128: one wave per SIMD, 256 key rows per block (dkdv128_bf16.hip); same arguments
-int launch_bwd_dkdv128_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
+// head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments
+int launch_bwd_dkdv_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
                             int load_acc, int store_final, float* parts);
 // adds up the partial tiles (tile_rows rows each) of divided key tiles, in slot order, into dK/dV or the
@@ -128,12 +128,12 @@ int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc
 int fwd_q_tile(int dtype, int head_dim);
 int dq_q_tile(int dtype, int head_dim);
 int dkdv_kv_tile(int dtype, int head_dim);
-// Which dK/dV kernel a bf16 problem uses: the 256-key kernel with one wave per SIMD (head dim 128
-// only) or the 128-key kernel.  One switch for the launch code and for the choice of the tile lists.
-#ifndef SLIMATTN_DKDV128
-#define SLIMATTN_DKDV128 1
+// Which dK/dV kernel a bf16 problem uses: the 256-key kernel with one wave per SIMD (head dims 128 and
+// 64) or the 128-key kernel.  One switch for the launch code and for the choice of the tile lists.
+#ifndef SLIMATTN_DKDV_WIDE
+#define SLIMATTN_DKDV_WIDE 1
 #endif
-constexpr bool kDkdv128Enabled = SLIMATTN_DKDV128 != 0;
-inline bool use_dkdv128(int dtype, int head_dim) { return kDkdv128Enabled && dtype == SLIMATTN_BF16 && head_dim == 128; }
+constexpr bool kDkdvWideEnabled = SLIMATTN_DKDV_WIDE != 0;
+inline bool use_dkdv_wide(int dtype, int head_dim) { return kDkdvWideEnabled && dtype == SLIMATTN_BF16 && (head_dim == 128 || head_dim == 64); }
 
 }  // namespace slimattn
