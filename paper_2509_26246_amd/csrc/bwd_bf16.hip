@@ -112,16 +112,46 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
     dsf[2 * b + 1] = pack8(sc, 8);
     __builtin_amdgcn_s_setprio(0);
   }
-  // dQ^T += K^T dS^T: one batch of four K^T fragments (the four 16-key steps) per head-dim block
-  Tr4 tb[NDB];
+  // dQ^T += K^T dS^T: one batch of K^T fragments per 16-key step j (one fragment per head-dim block), so that
+  // consecutive products go to different accumulators (a product on the accumulator of the one right
+  // before it has to wait for that one's result)
   constexpr int kStep = 16 * kRowBytes;
-  tr4_issue<0, kStep, 2 * kStep, 3 * kStep>(pkt[0][0], pkt[0][1], tb[0]);
+  if constexpr (NDB == 4) {
+    Tr4 tb[4];
+    auto issue = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      static_for<0, NDB>([&](auto dc) {
+        constexpr int db = decltype(dc)::value;
+        tr1_issue<j * kStep>(pkt[db][0], tb[j].r[2 * db]);
+        tr1_issue<j * kStep>(pkt[db][1], tb[j].r[2 * db + 1]);
+      });
+    };
+    issue(IC<0>{});
+    static_for<0, 4>([&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      if constexpr (j + 1 < 4) issue(IC<j + 1>{});
+      tr4_wait_n<(j + 1 < 4) ? 8 : 0>(tb[j]);
 #pragma unroll
-  for (int db = 0; db < NDB; ++db) {
-    if (db + 1 < NDB) tr4_issue_wait<0, kStep, 2 * kStep, 3 * kStep>(pkt[db + 1][0], pkt[db + 1][1], tb[db + 1], tb[db]);
-    else tr4_wait(tb[db]);
+      for (int db = 0; db < NDB; ++db) acc[db] = mfma32(tr4_frag(tb[j], db), dsf[j], acc[db]);
+    });
+  } else {
+    Tr2 tb[4];
+    auto issue = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      static_for<0, NDB>([&](auto dc) {
+        constexpr int db = decltype(dc)::value;
+        tr1_issue<j * kStep>(pkt[db][0], tb[j].r[2 * db]);
+        tr1_issue<j * kStep>(pkt[db][1], tb[j].r[2 * db + 1]);
+      });
+    };
+    issue(IC<0>{});
+    static_for<0, 4>([&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      if constexpr (j + 1 < 4) issue(IC<j + 1>{});
+      lds_wait<(j + 1 < 4) ? 4 : 0>(tb[j]);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[db] = mfma32(tr4_frag(tb[db], j), dsf[j], acc[db]);
+      for (int db = 0; db < NDB; ++db) acc[db] = mfma32(tr2_frag(tb[j], db), dsf[j], acc[db]);
+    });
   }
 }
 

@@ -173,6 +173,15 @@ __device__ __forceinline__ void tr4_wait(Tr4& p) {
                  "+v"(p.r[7]));
 }
 
+// Wait until at most N LDS operations issued after batch `p` are outstanding (`p` has then landed).
+template <int N>
+__device__ __forceinline__ void tr4_wait_n(Tr4& p) {
+  asm volatile("s_waitcnt lgkmcnt(%[n])"
+               : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]), "+v"(p.r[4]), "+v"(p.r[5]), "+v"(p.r[6]),
+                 "+v"(p.r[7])
+               : [n] "n"(N));
+}
+
 // Two-fragment variant (four loads per batch) for kernels that are short of registers.
 struct Tr2 { short4v r[4]; };
 __device__ __forceinline__ bf16x8 tr2_frag(const Tr2& t, int j) {
