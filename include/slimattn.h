@@ -149,9 +149,8 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
 void slimattn_tables_destroy(slimattn_tables* t);
 
 /* Counts held by a handle: what = 0 tokens, 1 samples, 2 slices, 3 forward units, 4 backward units,
- * 5..8 (128-row tiles) and 9..12 (256-row tiles): key tiles of the whole-list scope whose dK/dV work is
- * divided among several blocks when the launch has 1, 2, 4, >= 8 KV heads (heavy-tile balancing;
- * informational). */
+ * 5..8: 256-row key tiles of the whole-list scope whose dK/dV work is divided among several blocks
+ * when the launch has 1, 2, 4, >= 8 KV heads (heavy-tile balancing; informational). */
 int64_t slimattn_tables_count(const slimattn_tables* t, int what);
 
 /* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators, the per-row statistics in

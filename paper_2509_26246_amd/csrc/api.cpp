@@ -111,7 +111,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   float* acc_dv = acc_dk + acc_elems;
   float* delta = (float*)((char*)workspace + align_up(2 * acc_elems * sizeof(float)));
   float* lse2 = (float*)((char*)delta + align_up(T * p->n_q_heads * sizeof(float)));   // bf16 path: lse in log2 units
-  // -lse2, -delta as bf16 triples, 16 bytes per row and head (read by the 256-key dK/dV kernel only)
+  // -lse2, -delta as bf16 triples, 16 bytes per row and head (bf16 path: read by the dK/dV kernel)
   void* stat3 = (char*)lse2 + align_up(T * p->n_q_heads * sizeof(float));
   float* parts = (float*)((char*)stat3 + align_up(T * p->n_q_heads * 16));              // partial tiles of divided key tiles
   const int sc = split_class(p->n_kv_heads);
@@ -123,7 +123,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
     rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
       return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
-                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2, use_dkdv_wide(p->dtype, p->head_dim) ? stat3 : nullptr);
+                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2, stat3);
     }));
     if (rc != SLIMATTN_OK) return rc;
   }
@@ -141,11 +141,8 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
       return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
                                        delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
                                        store_final)
-                 : use_dkdv_wide(p->dtype, p->head_dim)
-                     ? launch_bwd_dkdv_wide_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
-                                               store_final, parts)
-                     : launch_bwd_dkdv_bf16(ctx, q, k, v, dO, lse2, delta, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc,
-                                            store_final, parts);
+                 : launch_bwd_dkdv_wide_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc, store_final,
+                                             parts);
     });
   };
   // bf16: the key-tile list in which heavy tiles are divided among several blocks, followed by the

@@ -21,11 +21,6 @@ namespace slimattn {
 namespace {
 
 constexpr int kDqBQ = 128, kDqBK = 64;
-constexpr int kKvOwn = 128;
-static_assert(kKvOwn == kSplitTileRows[0], "divided key-tile lists are built for this tile");
-// query rows per step of the dK/dV walk: at head_dim 128 the wave's V fragments live in LDS and the
-// step is 32 rows, which keeps the kernel at two waves per SIMD without register spills
-template <int D> struct DkdvCfg { static constexpr int kQStep = D == 128 ? 32 : 64; static constexpr bool kVInLds = D == 128; };
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------------
@@ -240,284 +235,6 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// One 32-row query block (QB) of the step staged in LDS buffer BUF against this wave's 32 keys.
-// MASKED blocks touch the diagonal or the end of the query run: rows before the key or at/after
-// q_hi contribute nothing.
-// pq[ks]: this lane's Q-fragment address (buffer 0, query block 0, head-dim step ks); the dO tile
-// has the same layout kTileBytes further on, buffer 1 kBufBytes further on.  pqt[db][0..1]:
-// Q^T-fragment address pair.  v_rel: byte distance from pq[] to this wave's V fragments (when the
-// V tile lives in LDS).
-template <int D, bool MASKED, int QB, int BUF>
-__device__ __forceinline__ void dkdv_block(const lds_cptr (&pq)[D / 16], const lds_cptr (&pqt)[D / 32][2], int v_rel,
-                                           const float* s_lse, const float* s_delta, const bf16x8 (&kf)[D / 16],
-                                           const bf16x8 (&vf)[D / 16], floatx16 (&dk)[D / 32], floatx16 (&dv)[D / 32],
-                                           int rel_lo, int rel_hi, int half) {
-  constexpr int kQStep = DkdvCfg<D>::kQStep;
-  constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes;
-  constexpr int qb = QB, qoff = BUF * kBufBytes + QB * 32 * kRowBytes;
-  // S = Q K^T - lse in log2 units (kf holds k * scale * log2 e); the accumulator starts at -lse of
-  // its row: local row 32 qb + 8 (r/4) + 4 half + r%4
-  floatx16 s;
-#pragma unroll
-  for (int gq = 0; gq < 4; ++gq) {
-    const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qb + 8 * gq + 4 * half]);
-#pragma unroll
-    for (int x = 0; x < 4; ++x) s[4 * gq + x] = -l4[x];
-  }
-  {   // batches of two Q fragments
-    R2 rb[NKS / 2];
-    r2_issue<qoff, qoff>(pq[0], pq[1], rb[0]);
-#pragma unroll
-    for (int j = 0; j < NKS / 2; ++j) {
-      if (j + 1 < NKS / 2) r2_issue_wait<qoff, qoff>(pq[2 * j + 2], pq[2 * j + 3], rb[j + 1], rb[j]);
-      else r2_wait(rb[j]);
-      s = mfma32(rb[j].f[0], kf[2 * j], s);
-      s = mfma32(rb[j].f[1], kf[2 * j + 1], s);
-    }
-  }
-  // P = exp(S - lse)
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int c = 32 * qb + 8 * (r >> 2) + (r & 3);                 // c + 4*half = local row
-    const float p = __builtin_amdgcn_exp2f(s[r]);
-    s[r] = (MASKED && (c < rel_lo || c >= rel_hi)) ? 0.f : p;
-  }
-  const bf16x8 pf0 = pack8(s, 0), pf1 = pack8(s, 8);
-  floatx16 dp;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) dp[r] = 0.f;
-  // dP = dO V^T
-  constexpr int doff = qoff + kTileBytes;
-  if (DkdvCfg<D>::kVInLds) {   // both operands come from LDS: one (dO fragment, V fragment) pair per batch
-    R2 rb[NKS];
-    r2_issue<doff, 0>(pq[0], pq[0] + v_rel, rb[0]);
-#pragma unroll
-    for (int j = 0; j < NKS; ++j) {
-      if (j + 1 < NKS) r2_issue_wait<doff, 0>(pq[j + 1], pq[j + 1] + v_rel, rb[j + 1], rb[j]);
-      else r2_wait(rb[j]);
-      dp = mfma32(rb[j].f[0], rb[j].f[1], dp);
-    }
-  } else {                     // batches of two dO fragments against the V fragments held in registers
-    R2 rb[NKS / 2];
-    r2_issue<doff, doff>(pq[0], pq[1], rb[0]);
-#pragma unroll
-    for (int j = 0; j < NKS / 2; ++j) {
-      if (j + 1 < NKS / 2) r2_issue_wait<doff, doff>(pq[2 * j + 2], pq[2 * j + 3], rb[j + 1], rb[j]);
-      else r2_wait(rb[j]);
-      dp = mfma32(rb[j].f[0], vf[2 * j], dp);
-      dp = mfma32(rb[j].f[1], vf[2 * j + 1], dp);
-    }
-  }
-#pragma unroll
-  for (int gq = 0; gq < 4; ++gq) {
-    const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qb + 8 * gq + 4 * half]);
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int r = 4 * gq + x;
-      dp[r] = s[r] * (dp[r] - d4[x]);                                // dS = P (dP - delta)
-    }
-  }
-  const bf16x8 dsf0 = pack8(dp, 0), dsf1 = pack8(dp, 8);
-  // dV^T += dO^T P and dK^T += Q^T dS.  Per head-dim block and 16-row step one batch of two
-  // transposed fragments (dO^T, Q^T); batch b = 2 * db + step.
-  Tr2 tb[2 * NDB];
-  constexpr int kQ0 = qoff, kQ1 = kQ0 + 16 * kRowBytes;
-  tr2_issue<kQ0 + kTileBytes, kQ0>(pqt[0][0], pqt[0][1], tb[0]);
-#pragma unroll
-  for (int b = 0; b < 2 * NDB; ++b) {
-    const int db = b >> 1;
-    if (b + 1 < 2 * NDB) {
-      if (b & 1) tr2_issue_wait<kQ0 + kTileBytes, kQ0>(pqt[db + 1][0], pqt[db + 1][1], tb[b + 1], tb[b]);
-      else tr2_issue_wait<kQ1 + kTileBytes, kQ1>(pqt[db][0], pqt[db][1], tb[b + 1], tb[b]);
-    } else {
-      tr2_wait(tb[b]);
-    }
-    dv[db] = mfma32(tr2_frag(tb[b], 0), (b & 1) ? pf1 : pf0, dv[db]);
-    dk[db] = mfma32(tr2_frag(tb[b], 1), (b & 1) ? dsf1 : dsf0, dk[db]);
-  }
-}
-
-template <int D>
-__global__ __launch_bounds__(256, 2) void dkdv_bf16_kernel(
-    const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
-    const float* __restrict__ lse2, const float* __restrict__ delta, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
-    bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
-    int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
-  constexpr int NKS = D / 16, NDB = D / 32, kQStep = DkdvCfg<D>::kQStep;
-  constexpr bool kVInLds = DkdvCfg<D>::kVInLds;
-  constexpr int kTileBytes = kQStep * D * 2, kBufBytes = 2 * kTileBytes, kVBytes = kVInLds ? kKvOwn * D * 2 : 0;
-  __shared__ __attribute__((aligned(1024))) char smem[2 * kBufBytes + kVBytes];   // [buffer][Q tile, dO tile], V tile
-  __shared__ __attribute__((aligned(16))) float s_stat[2][2][kQStep];             // [buffer][lse2, delta][row]
-
-  const int g = Hq / Hkv;
-  // one block per (key tile, kv head); kv heads of one tile adjacent, heavy tiles first
-  const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
-  if (item_idx >= n_items) return;
-  const KvItem it = items[item_idx];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  const int kv0w = it.kv_row0 + 32 * wave, my_key = kv0w + l32, kv_end = it.kv_row0 + it.kv_rows;
-  const int ld_key = min(my_key, T - 1);
-  LDS_PTR(char) lds = (LDS_PTR(char))smem;
-
-  // Flattened walk: runs from the last to the first, inside a run steps of kQStep rows from the top
-  // down, inside a step the heads of the group.  Every key tile of a sample thus starts at the
-  // sample's last rows and moves towards its own rows, so the blocks that run side by side read the
-  // same Q/dO rows at about the same time and share them through L2.  Steps are aligned to the
-  // tile's first row; rows are addressed relative to it (every run of the item lies at or after it).
-  int sgi = it.seg_end - 1, hh = 0;
-  Seg sg = segs[sgi];
-  int lo = max(sg.q_lo, it.kv_row0);
-  int n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
-  int i0 = lo + n * kQStep;
-  bool have = true;                                   // a key tile always has at least its own rows
-  const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
-  const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
-  const int head_bytes = D * 2;
-  float pre_stat = 0.f;                               // next step's lse2 (threads 0..kQStep-1) / delta (next kQStep)
-  // Row statistics first (through a register, written to LDS when the step ends), then the tiles
-  // straight into LDS buffer buf_.
-#define SLIMATTN_STAGE(buf_, row0_, head_)                                                                     \
-  do {                                                                                                         \
-    if (tid < 2 * kQStep) {                                                                                    \
-      const int r_ = min((row0_) + (tid & (kQStep - 1)), T - 1);                                               \
-      pre_stat = (tid < kQStep ? lse2 : delta)[(size_t)(head_) * T + r_];                                      \
-    }                                                                                                          \
-    TileSource a_ = srcQ, b_ = srcDO;                                                                          \
-    a_.voff += (head_) * head_bytes;                                                                           \
-    b_.voff += (head_) * head_bytes;                                                                           \
-    stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes, a_, (row0_) - it.kv_row0, tid);                       \
-    stage_tile<D, kQStep, 256>(lds + (buf_) * kBufBytes + kTileBytes, b_, (row0_) - it.kv_row0, tid);          \
-  } while (0)
-#define SLIMATTN_COMMIT(buf_)                                                                                  \
-  do {                                                                                                         \
-    if (tid < 2 * kQStep) (&s_stat[(buf_)][0][0])[tid] = pre_stat;                                             \
-  } while (0)
-  SLIMATTN_STAGE(0, i0, hk * g + hh);
-  if (kVInLds) {   // the block's 128 V rows, read as fragments by every step
-    const TileSource srcV = make_tile_source<D, 256>(v, it.kv_row0, Hkv, hk, T, tid);
-    stage_tile<D, kKvOwn, 256>(lds + 2 * kBufBytes, srcV, 0, tid);
-  }
-
-  bf16x8 kf[NKS], vf[NKS];
-  {
-    const size_t off = ((size_t)ld_key * Hkv + hk) * D + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      kf[ks] = scale8(*reinterpret_cast<const bf16x8*>(k + off + 16 * ks), scale * kLog2e);
-      if (!kVInLds) vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
-    }
-  }
-  lds_cptr pq[NKS], pqt[NDB][2];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) pq[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
-#pragma unroll
-  for (int db = 0; db < NDB; ++db) lds_tr_ptrs<D>(lds, 32 * db, lane, pqt[db][0], pqt[db][1]);
-  int v_rel = 2 * kBufBytes + wave * 32 * D * 2;      // the swizzle of row 32*wave + l32 equals that of row l32
-  floatx16 dk[NDB], dv[NDB];
-#pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
-  SLIMATTN_COMMIT(0);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-
-  // One step on buffer BUF_: advance the walk and start fetching the next step into the other
-  // buffer, multiply, publish the next step's row statistics, wait, barrier.
-#define SLIMATTN_QBLOCK(QB_, BUF_)                                                                             \
-  do {                                                                                                         \
-    const int r0 = cur_i0 + 32 * (QB_);            /* first row of the block */                                \
-    if (!(r0 + 31 < kv0w || r0 >= cur_hi)) {       /* wave-uniform: something at or after the wave's keys */   \
-      if (r0 >= kv0w + 31 && r0 + 32 <= cur_hi)                                                                \
-        dkdv_block<D, false, QB_, BUF_>(pq, pqt, v_rel, s_stat[BUF_][0], s_stat[BUF_][1], kf, vf, dk, dv, rel_lo, \
-                                        rel_hi, half);                                                         \
-      else                                                                                                     \
-        dkdv_block<D, true, QB_, BUF_>(pq, pqt, v_rel, s_stat[BUF_][0], s_stat[BUF_][1], kf, vf, dk, dv, rel_lo, \
-                                       rel_hi, half);                                                          \
-    }                                                                                                          \
-  } while (0)
-#define SLIMATTN_STEP(BUF_)                                                                                    \
-  do {                                                                                                         \
-    const int cur_i0 = i0, cur_hi = sg.q_hi;                                                                   \
-    if (++hh == g) {                                                                                           \
-      hh = 0;                                                                                                  \
-      if (--n < 0) {                                                                                           \
-        if (--sgi < it.seg_begin) {                                                                            \
-          have = false;                                                                                        \
-        } else {                                                                                               \
-          sg = segs[sgi];                                                                                      \
-          lo = max(sg.q_lo, it.kv_row0);                                                                       \
-          n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;                                                        \
-        }                                                                                                      \
-      }                                                                                                        \
-      i0 = lo + n * kQStep;                                                                                    \
-    }                                                                                                          \
-    if (have) SLIMATTN_STAGE((BUF_) ^ 1, i0, hk * g + hh);                                                     \
-    asm volatile("" : "+v"(v_rel));                /* keep the V fragment addresses from being hoisted */     \
-    /* local rows [rel_lo, rel_hi) minus 4*half contribute: row >= key and row < end of the run */           \
-    const int rel_lo = my_key - cur_i0 - 4 * half, rel_hi = cur_hi - cur_i0 - 4 * half;                        \
-    SLIMATTN_QBLOCK(0, BUF_);                                                                                  \
-    if (kQStep == 64) SLIMATTN_QBLOCK(kQStep == 64 ? 1 : 0, BUF_);                                             \
-    if (have) SLIMATTN_COMMIT((BUF_) ^ 1);                                                                     \
-    __builtin_amdgcn_s_waitcnt(0);                                                                             \
-    __syncthreads();                                                                                           \
-  } while (0)
-  while (true) {                                      // `have` is uniform across the block
-    SLIMATTN_STEP(0);
-    if (!have) break;
-    SLIMATTN_STEP(1);
-    if (!have) break;
-  }
-#undef SLIMATTN_STEP
-#undef SLIMATTN_QBLOCK
-#undef SLIMATTN_COMMIT
-#undef SLIMATTN_STAGE
-
-  if (it.slot >= 0) {
-    // one part of a divided key tile: fp32 partial tile [slot][kv head][dK, dV][128 rows][D]
-    float* pk_ = parts + ((size_t)it.slot * Hkv + hk) * (2 * kKvOwn * D) + (size_t)(32 * wave + l32) * D;
-    float* pv_ = pk_ + kKvOwn * D;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const int off = 32 * db + 8 * gq + 4 * half;
-        floatx4 a, b;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) { a[x] = dk[db][4 * gq + x] * scale; b[x] = dv[db][4 * gq + x]; }
-        *reinterpret_cast<floatx4*>(pk_ + off) = a;
-        *reinterpret_cast<floatx4*>(pv_ + off) = b;
-      }
-  } else if (my_key < kv_end) {
-    const size_t base = ((size_t)my_key * Hkv + hk) * D;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const size_t off = base + 32 * db + 8 * gq + 4 * half;
-        floatx4 a, b;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) { a[x] = dk[db][4 * gq + x] * scale; b[x] = dv[db][4 * gq + x]; }
-        if (load_acc) {
-          const floatx4 pa = *reinterpret_cast<const floatx4*>(acc_dk + off);
-          const floatx4 pb = *reinterpret_cast<const floatx4*>(acc_dv + off);
-          a += pa;
-          b += pb;
-        }
-        if (store_final) {
-          bf16x4 wa, wb;
-#pragma unroll
-          for (int x = 0; x < 4; ++x) { wa[x] = (bf16)a[x]; wb[x] = (bf16)b[x]; }
-          *reinterpret_cast<bf16x4*>(dK + off) = wa;
-          *reinterpret_cast<bf16x4*>(dV + off) = wb;
-        } else {
-          *reinterpret_cast<floatx4*>(acc_dk + off) = a;
-          *reinterpret_cast<floatx4*>(acc_dv + off) = b;
-        }
-      }
-  }
-}
-
 // Sum of the partial tiles of a divided key tile, in slot order (fixed, so the result does not
 // depend on which block finished first), added to the fp32 accumulators or written as bf16.
 // One block per (tile, kv head); a thread owns four consecutive columns of a row.
@@ -562,7 +279,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 }  // namespace
 
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
-int dkdv_kv_tile(int dtype, int head_dim) { return dtype == SLIMATTN_F32 ? 64 : use_dkdv_wide(dtype, head_dim) ? 256 : kKvOwn; }
+int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kSplitTileRows[0]; }   // bf16: the dK/dV kernel's 256 key rows per block
 
 int launch_bwd_delta_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, float* delta, float* lse2,
                           void* stat3) {
@@ -593,23 +310,6 @@ int launch_bwd_dq_bf16(const LaunchCtx& c, const void* q, const void* k, const v
     hipLaunchKernelGGL(dq_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (const bf16*)dO, lse, delta, (bf16*)dQ, items, n_items, (int)c.T, p.n_q_heads,
                        p.n_kv_heads, p.scale);
-  return (int)hipGetLastError();
-}
-
-int launch_bwd_dkdv_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const float* lse,
-                         const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                         int n_items, const Seg* segs, int load_acc, int store_final, float* parts) {
-  if (n_items == 0) return 0;
-  const slimattn_params& p = *c.p;
-  const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
-  if (p.head_dim == 128)
-    hipLaunchKernelGGL(dkdv_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
-  else
-    hipLaunchKernelGGL(dkdv_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (const bf16*)dO, lse, delta, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
   return (int)hipGetLastError();
 }
 

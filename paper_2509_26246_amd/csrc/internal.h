@@ -35,12 +35,12 @@ struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts; };
 // Divided lists exist for the 128- and 256-row key tiles (the two bf16 dK/dV kernels) and four classes
 // of KV-head count (1, 2, 4, >= 8): a launch has items x KV heads blocks, so the fewer KV heads, the
 // fewer blocks share the work and the more a single long sample's first tiles dominate the makespan.
-constexpr int kNumSplitTiles = 2;
-constexpr int kSplitTileRows[kNumSplitTiles] = {128, 256};
-constexpr int kSplitBlockSlots[kNumSplitTiles] = {512, 192};   // slots the per-slot share is taken over: the 128-key kernel's
-                                                                // resident blocks; 3/4 of the 256-key kernel's (measured: its
-                                                                // parts cost more to set up, so it divides less)
-inline int split_tile_index(int rows) { return rows == 128 ? 0 : rows == 256 ? 1 : -1; }
+constexpr int kNumSplitTiles = 1;                               // key-tile sizes for which divided lists are built
+constexpr int kSplitTileRows[kNumSplitTiles] = {256};           // the bf16 dK/dV kernel's tile
+// Slots the per-slot share of the work is taken over: 3/4 of the kernel's 256 resident blocks (measured: a
+// part costs a V tile, K fragments and an fp32 partial tile to set up, and dividing more finely lost 1-4 %).
+constexpr int kSplitBlockSlots[kNumSplitTiles] = {192};
+inline int split_tile_index(int rows) { return rows == 256 ? 0 : -1; }
 constexpr int kNumSplitClasses = 4;
 inline int split_class(int n_kv_heads) { return n_kv_heads >= 8 ? 3 : n_kv_heads >= 4 ? 2 : n_kv_heads >= 2 ? 1 : 0; }
 
@@ -56,7 +56,7 @@ struct ScopeLists {
   std::vector<KvItem> split_items[kNumSplitTiles][kNumSplitClasses];
   std::vector<int32_t> reduce_off[kNumSplitTiles][kNumSplitClasses];
   std::vector<KvReduce> reduce_items[kNumSplitTiles][kNumSplitClasses];
-  int32_t max_slots[kNumSplitTiles][kNumSplitClasses] = {{0, 0, 0, 0}, {0, 0, 0, 0}};   // most partial tiles any one scope needs
+  int32_t max_slots[kNumSplitTiles][kNumSplitClasses] = {{0, 0, 0, 0}};   // most partial tiles any one scope needs
 };
 
 struct DeviceLists {                            // device mirrors (pointers into one allocation)
@@ -111,9 +111,6 @@ int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, const
 // the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
 int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
                        const float* delta, void* dQ, const QItem* items, int n_items);
-int launch_bwd_dkdv_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
-                         const float* delta, float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items,
-                         int n_items, const Seg* segs, int load_acc, int store_final, float* parts);
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments
 int launch_bwd_dkdv_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
@@ -128,12 +125,4 @@ int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc
 int fwd_q_tile(int dtype, int head_dim);
 int dq_q_tile(int dtype, int head_dim);
 int dkdv_kv_tile(int dtype, int head_dim);
-// Which dK/dV kernel a bf16 problem uses: the 256-key kernel with one wave per SIMD (head dims 128 and
-// 64) or the 128-key kernel.  One switch for the launch code and for the choice of the tile lists.
-#ifndef SLIMATTN_DKDV_WIDE
-#define SLIMATTN_DKDV_WIDE 1
-#endif
-constexpr bool kDkdvWideEnabled = SLIMATTN_DKDV_WIDE != 0;
-inline bool use_dkdv_wide(int dtype, int head_dim) { return kDkdvWideEnabled && dtype == SLIMATTN_BF16 && (head_dim == 128 || head_dim == 64); }
-
 }  // namespace slimattn

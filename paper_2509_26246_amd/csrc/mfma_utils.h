@@ -189,24 +189,6 @@ __device__ __forceinline__ bf16x8 tr2_frag(const Tr2& t, int j) {
   short8v x = __builtin_shufflevector(t.r[2 * j], t.r[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, x);
 }
-#define SLIMATTN_TR2_READS                                   \
-  "ds_read_b64_tr_b16 %0, %[p0] offset:%[o0]\n\t"            \
-  "ds_read_b64_tr_b16 %1, %[p1] offset:%[o0]\n\t"            \
-  "ds_read_b64_tr_b16 %2, %[p0] offset:%[o1]\n\t"            \
-  "ds_read_b64_tr_b16 %3, %[p1] offset:%[o1]\n\t"
-template <int O0, int O1>
-__device__ __forceinline__ void tr2_issue(lds_cptr p0, lds_cptr p1, Tr2& n) {
-  asm volatile(SLIMATTN_TR2_READS
-               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3])
-               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1));
-}
-template <int O0, int O1>
-__device__ __forceinline__ void tr2_issue_wait(lds_cptr p0, lds_cptr p1, Tr2& n, Tr2& p) {
-  asm volatile(SLIMATTN_TR2_READS "s_waitcnt lgkmcnt(4)"
-               : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3]), "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]),
-                 "+v"(p.r[3])
-               : [p0] "v"(p0), [p1] "v"(p1), [o0] "n"(O0), [o1] "n"(O1));
-}
 // Two fragments from two different address pairs at one byte offset (e.g. the same key step of two
 // head-dim blocks, which feed two independent accumulators).
 template <int O>
@@ -217,9 +199,6 @@ __device__ __forceinline__ void tr2x_issue(lds_cptr a0, lds_cptr a1, lds_cptr b0
                "ds_read_b64_tr_b16 %3, %[b1] offset:%[o]"
                : "=&v"(n.r[0]), "=&v"(n.r[1]), "=&v"(n.r[2]), "=&v"(n.r[3])
                : [a0] "v"(a0), [a1] "v"(a1), [b0] "v"(b0), [b1] "v"(b1), [o] "n"(O));
-}
-__device__ __forceinline__ void tr2_wait(Tr2& p) {
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(p.r[0]), "+v"(p.r[1]), "+v"(p.r[2]), "+v"(p.r[3]));
 }
 
 // Row-fragment batches through inline asm (same reason and same protocol as the transposed ones):
@@ -241,14 +220,6 @@ __device__ __forceinline__ void r2_wait(R2& p) { asm volatile("s_waitcnt lgkmcnt
 
 // Four-fragment row batches.
 struct R4 { bf16x8 f[4]; };
-template <int O0, int O1, int O2, int O3>
-__device__ __forceinline__ void r4_issue(lds_cptr a0, lds_cptr a1, lds_cptr a2, lds_cptr a3, R4& n) {
-  asm volatile("ds_read_b128 %0, %[a0] offset:%[o0]\n\tds_read_b128 %1, %[a1] offset:%[o1]\n\t"
-               "ds_read_b128 %2, %[a2] offset:%[o2]\n\tds_read_b128 %3, %[a3] offset:%[o3]"
-               : "=&v"(n.f[0]), "=&v"(n.f[1]), "=&v"(n.f[2]), "=&v"(n.f[3])
-               : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3), [o0] "n"(O0), [o1] "n"(O1), [o2] "n"(O2),
-                 [o3] "n"(O3));
-}
 
 // One transposed 64-bit read of a Tr2 batch (r[0], r[1]: first fragment from the two addresses of
 // the pair; r[2], r[3]: second fragment), for code that spreads the reads between other instructions.

@@ -274,7 +274,6 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
     case 3: return t->n_units[0];
     case 4: return t->n_units[1];
     case 5: case 6: case 7: case 8: return (int64_t)t->fused.reduce_items[0][what - 5].size();
-    case 9: case 10: case 11: case 12: return (int64_t)t->fused.reduce_items[1][what - 9].size();
     default: return -1;
   }
 }
