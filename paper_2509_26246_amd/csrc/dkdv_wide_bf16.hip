@@ -78,15 +78,14 @@ __device__ __forceinline__ void mfma_acc(floatx16& acc, bf16x8 a, bf16x8 b) {
 // product with a fragment of ones (ones_l picks the first triple, ones_d the second; zero in the upper
 // half-wave, whose copy of `stat` therefore does not count) puts their sums into every column of the
 // row.  That costs four products and no vector or LDS instruction, where loading the 64 accumulator
-// registers costs a quarter of the phase.  A row past the end of its query run comes with -2^100 in
-// place of -lse2 (and 0 for -delta; the caller's doing): its probabilities and dS are zero.  In
-// `masked` steps (the step's rows reach back to or before the wave's last key) the scores of rows
-// before the lane's key (local row - 4*half < rel_lo[kb]) are then set to -inf, with the same effect.
+// registers costs a quarter of the phase.  In `masked` steps the scores of pairs that do not count
+// (local row - 4*half outside [rel_lo[kb], rel_hi): before the lane's key, or past the end of the query
+// run) are then set to -inf, so that their probability and dS come out as zero.
 // One batch of LDS reads per head-dim step: the Q and dO fragments and the two V fragments.
 template <int D, class Between>
 __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS<D>], int v_rel, bf16x8 stat, uintx4 ones_l, uintx4 ones_d,
                                                const bf16x8 (&kf)[2][kNKS<D>], floatx16 (&s)[2], floatx16 (&dp)[2],
-                                               bool masked, const int (&rel_lo)[2], Between&& between) {
+                                               bool masked, const int (&rel_lo)[2], int rel_hi, Between&& between) {
   // Fragment i of head-dim step u: 0 Q rows, 1 dO rows, 2/3 the V rows of the two key blocks.  The
   // reads of step u + 2 are issued one behind each product of step u (an LDS read takes about twice the
   // issue time of a plain instruction: four in a row would outlast the product they follow); those of
@@ -107,17 +106,19 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS<D>], in
   static_for<0, 4>([&](auto ic) { issue_one(IC<1>{}, ic); });
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(dp[0]) : "v"(stat), "v"(ones_d));
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(dp[1]) : "v"(stat), "v"(ones_d));
-  if (masked) {
+  if (__builtin_expect(masked, 0)) {
     // the products above are asm statements: the compiler does not separate them from readers of
     // their results by the wait states the hardware needs
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb) {
+      const unsigned span = (unsigned)max(rel_hi - rel_lo[kb], 0);   // c - rel_lo in [0, span) <=> the pair counts
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int c = 8 * (r >> 2) + (r & 3);           // c + 4*half = local row
-        s[kb][r] = c >= rel_lo[kb] ? s[kb][r] : -INFINITY;
+        s[kb][r] = (unsigned)(c - rel_lo[kb]) < span ? s[kb][r] : -INFINITY;
       }
+    }
   }
   static_for<0, kNKS<D>>([&](auto uc) {
     constexpr int u = decltype(uc)::value;
@@ -270,15 +271,24 @@ __device__ __forceinline__ void dkdv_wide_block(
   int lo = max(sg.q_lo, it.kv_row0);
   int n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
   bool more = true;                                     // the walk has a step that was not handed out yet
-  auto next_step = [&](Step& d) -> bool {              // straight-line in the common case (same run, next head or step)
-    if (!more) return false;
-    d.i0 = lo + n * kQStep;
-    d.hi = sg.q_hi;
-    d.head = hk * g + hh;
-    const bool wrap = hh + 1 == g;
-    hh = wrap ? 0 : hh + 1;
+  // The next step of the walk, in three pieces (the loop runs each behind a different product; between
+  // pieces the values are pinned with empty asm statements so that the compiler leaves the arithmetic
+  // where it is written).  A step is only taken when `more`; otherwise d keeps its value.
+  auto next_step_a = [&](Step& d) -> bool {            // the step's coordinates
+    const bool ok = more;
+    d.i0 = __builtin_amdgcn_readfirstlane(ok ? lo + n * kQStep : d.i0);   // (block-uniform anyway: tells the compiler)
+    d.hi = __builtin_amdgcn_readfirstlane(ok ? sg.q_hi : d.hi);
+    d.head = __builtin_amdgcn_readfirstlane(ok ? hk * g + hh : d.head);
+    asm volatile("" : "+s"(d.i0), "+s"(d.hi), "+s"(d.head));
+    return ok;
+  };
+  auto next_step_b = [&](bool ok) {                     // move on: next head, or next 32 rows down
+    const bool wrap = ok && hh + 1 == g;
+    hh = !ok ? hh : wrap ? 0 : hh + 1;
     n -= wrap ? 1 : 0;
-    if (__builtin_expect(n < 0, 0)) {                   // the run is used up: the one before it, if any
+  };
+  auto next_step_c = [&](bool ok) {                     // the run is used up: the one before it, if any
+    if (__builtin_expect((int)ok & (int)(n < 0), 0)) {
       if (--sgi < it.seg_begin) {
         more = false;
       } else {
@@ -287,7 +297,12 @@ __device__ __forceinline__ void dkdv_wide_block(
         n = (sg.q_hi - lo + kQStep - 1) / kQStep - 1;
       }
     }
-    return true;
+  };
+  auto next_step = [&](Step& d) -> bool {
+    const bool ok = next_step_a(d);
+    next_step_b(ok);
+    next_step_c(ok);
+    return ok;
   };
 
   const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
@@ -299,8 +314,15 @@ __device__ __forceinline__ void dkdv_wide_block(
     stage_tile<D, kQStep, 256>(lds + st * kStageBytes<D>, a, d.i0 - it.kv_row0, tid);
     stage_tile<D, kQStep, 256>(lds + st * kStageBytes<D> + kTileBytes<D>, b, d.i0 - it.kv_row0, tid);
   };
-  // a step's statistics for this lane's row: -lse2, -delta as bf16 triples (rows past the end of the run: see the loop)
-  auto load_stat = [&](const Step& d) -> bf16x8 { return stat3[(size_t)d.head * T + min(d.i0 + l32, T - 1)]; };
+  // A step's statistics for this lane's row (-lse2, -delta as bf16 triples; rows past the end of the run
+  // are masked later), through a buffer descriptor: a per-lane byte offset (stat_voff) plus a scalar one.
+  const __amdgpu_buffer_rsrc_t stat_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)stat3, 0, (int)((size_t)T * Hq * 16), 0x00020000);
+  auto stat_voff = [&](const Step& d) -> int { return min(d.i0 + l32, T - 1) * 16; };
+  auto load_stat_at = [&](const Step& d, int voff) -> bf16x8 {
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
+    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(stat_rsrc, voff, d.head * T * 16, 0));
+  };
+  auto load_stat = [&](const Step& d) -> bf16x8 { return load_stat_at(d, stat_voff(d)); };
 
   Step d_s, d_n;                                        // the step whose scores come next, the step to stage
   next_step(d_s);                                       // a key tile always has at least its own rows
@@ -337,11 +359,14 @@ __device__ __forceinline__ void dkdv_wide_block(
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  // Masks of a step for this wave.  Causal: local rows >= rel_lo0 (+32 for the second key block) + 4*half
-  // count; `masked` (wave-uniform): the step has a row before the wave's last key.  End of the query run:
-  // the step's first `rows` rows exist (wave-uniform; < 32 only in a run's last step).
-  struct Mask { int rel_lo0, rows; bool masked; };
-  auto masks = [&](const Step& d) -> Mask { return Mask{kv0w + l32 - d.i0 - 4 * half, d.hi - d.i0, d.i0 < kv0w + 63}; };
+  // Masks of a step for this wave: local rows [rel_lo0 (+32 for the second key block), rel_hi) minus 4*half
+  // count (from the lane's key on, up to the end of the query run); `masked` (wave-uniform): the step has a
+  // row before the wave's last key or past the end of its run.  One flag, one branch per step: branches,
+  // taken or not, are among the most expensive instructions of this loop.
+  struct Mask { int rel_lo0, rel_hi; bool masked; };
+  auto masks = [&](const Step& d) -> Mask {
+    return Mask{kv0w + l32 - d.i0 - 4 * half, d.hi - d.i0 - 4 * half, d.i0 < kv0w + 63 || d.i0 + kQStep > d.hi};
+  };
   Mask m_s = masks(d_s), m_n = m_s;
   const int wave_off = __builtin_amdgcn_readfirstlane((tid >> 6) * 1024);   // this wave's lines within a staging pass
 
@@ -372,21 +397,31 @@ __device__ __forceinline__ void dkdv_wide_block(
     int voff_n = 0, soff_n = 0;
     Tr2 tb[kGradBatches<D>];                               // the gradient phase's batches of transposed fragments
     const int m0_n = st_n * kStageBytes<D> + wave_off;     // where this wave's lines of the first pass go
-    // slots of the pieces (behind score product k): spread out at d 128 (32 slots), packed at d 64 (16)
-    constexpr int kSlotNext = D == 128 ? 4 : 2, kSlotStat = D == 128 ? 6 : 3, kSlotAddr = D == 128 ? 8 : 4;
-    constexpr int kSlotLoad = D == 128 ? 9 : 5, kSlotMask = D == 128 ? 13 : 7, kSlotGrad = 4 * (kNKS<D> - 2);
+    // slots of the pieces (behind score product k): spread out at d 128 (32 slots), packed at d 64 (16).
+    // A piece is a handful of instructions: what does not fit behind its product delays the next one.
+    constexpr int kSlotWalkA = D == 128 ? 4 : 2, kSlotWalkB = D == 128 ? 5 : 3, kSlotWalkC = D == 128 ? 6 : 3;
+    constexpr int kSlotStatA = D == 128 ? 7 : 4, kSlotStat = D == 128 ? 8 : 5, kSlotAddr = D == 128 ? 9 : 4;
+    constexpr int kSlotLoad = D == 128 ? 10 : 6, kLoadStride = D == 128 ? 2 : 1, kSlotMask = D == 128 ? 18 : 7;
+    constexpr int kSlotGrad = 4 * (kNKS<D> - 2);
     constexpr int kPasses = kTileBytes<D> / 4096;         // staging loads per tile (256 threads x 16 bytes each)
+    bool ok_n = false;
+    int stat_off = 0;
     auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
       constexpr int k = decltype(kc)::value;
       if constexpr (k < kNDB<D>) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
-      if constexpr (k == kSlotNext) have_n = have_s && next_step(d_n);
-      if constexpr (k == kSlotStat) stat_n = load_stat(d_n);   // d_n always names a real step (the last one, when the walk has ended)
+      if constexpr (k == kSlotWalkA) { ok_n = next_step_a(d_n); have_n = have_s && ok_n; }
+      if constexpr (k == kSlotWalkB) next_step_b(ok_n);
+      if constexpr (k == kSlotWalkC) next_step_c(ok_n);
+      if constexpr (k == kSlotStatA) { stat_off = stat_voff(d_n); asm volatile("" : "+v"(stat_off)); }
+      if constexpr (k == kSlotStat) stat_n = load_stat_at(d_n, stat_off);   // d_n always names a real step (the last one, when the walk has ended)
       if constexpr (k == kSlotAddr) {
         voff_n = srcQ.voff + d_n.head * kRowBytes<D>;   // the Q and dO sources differ in their descriptors only
-        soff_n = (d_n.i0 - it.kv_row0) * srcQ.row_bytes;
+        soff_n = __builtin_amdgcn_readfirstlane((d_n.i0 - it.kv_row0) * srcQ.row_bytes);
+        asm volatile("" : "+v"(voff_n), "+s"(soff_n));
       }
-      if constexpr (k >= kSlotLoad && k < kSlotLoad + 2 * kPasses) {   // one load each: the passes of the Q tile, then of the dO tile
-        constexpr int tile = (k - kSlotLoad) / kPasses, pass = (k - kSlotLoad) % kPasses;
+      if constexpr (k >= kSlotLoad && k < kSlotLoad + 2 * kPasses * kLoadStride && (k - kSlotLoad) % kLoadStride == 0) {
+        // one load each: the passes of the Q tile, then of the dO tile
+        constexpr int x = (k - kSlotLoad) / kLoadStride, tile = x / kPasses, pass = x % kPasses;
         constexpr int kRowsPerPass = 4096 / kRowBytes<D>;
         // (when the walk has ended d_n still names the last step: its tile is staged once more, into a stage nobody reads)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes<D> + pass * 4096, 16,
@@ -402,14 +437,7 @@ __device__ __forceinline__ void dkdv_wide_block(
     floatx16 s[2], dp[2];
     uintx4 npf[2][2], nds[2][2];
     const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
-    if (m_s.rows < kQStep) {
-      // a run's last step: rows past its end get -2^100 in place of -lse2 and 0 for -delta, so their
-      // probabilities and dS come out as zero (the wait states: a vector write right before an asm product)
-      const bf16x8 gone = __builtin_bit_cast(bf16x8, uintx4{0x0000F180u, 0u, 0u, 0u});
-      stat_s = l32 < m_s.rows ? stat_s : gone;
-      asm volatile("s_nop 7" : "+v"(stat_s));
-    }
-    score_products<D>(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, between);
+    score_products<D>(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, m_s.rel_hi, between);
     gradient_products<D, first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -424,12 +452,12 @@ __device__ __forceinline__ void dkdv_wide_block(
     have_s = have_n;
     dt_pend = first ? 0 : (st_s == 0 ? -2 * kStageBytes<D> : kStageBytes<D>);   // pqt moves to the stage just scored
     st_s = st_n;
-    // the last products' results must have landed before any vector instruction reads them (the
-    // compiler does not know that the asm statements are matrix products): explicit wait states
-    if (!again) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
   };
   iteration(IC<1>{});
   while (again) iteration(IC<0>{});
+  // the last products' results must have landed before any vector instruction reads them (the
+  // compiler does not know that the asm statements are matrix products): explicit wait states
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
 
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
