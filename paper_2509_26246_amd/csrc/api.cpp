@@ -110,9 +110,8 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   float* acc_dk = (float*)workspace;
   float* acc_dv = acc_dk + acc_elems;
   float* delta = (float*)((char*)workspace + align_up(2 * acc_elems * sizeof(float)));
-  float* lse2 = (float*)((char*)delta + align_up(T * p->n_q_heads * sizeof(float)));   // bf16 path: lse in log2 units
-  // -lse2, -delta as bf16 triples, 16 bytes per row and head (bf16 path: read by the dK/dV kernel)
-  void* stat3 = (char*)lse2 + align_up(T * p->n_q_heads * sizeof(float));
+  // bf16 path: -lse*log2e and -delta as bf16 triples, 16 bytes per row and head (written by the dQ kernel, read by the dK/dV kernel)
+  void* stat3 = (char*)delta + align_up(T * p->n_q_heads * sizeof(float));
   float* parts = (float*)((char*)stat3 + align_up(T * p->n_q_heads * 16));              // partial tiles of divided key tiles
   const int sc = split_class(p->n_kv_heads);
   const LaunchCtx ctx{p, stream, t->total_tokens};
@@ -120,11 +119,11 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   const bool whole = lo == 0 && hi == n_units;
   const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
 
-  if (lo == 0) {   // row statistic delta_i = dO_i . o_i for every row and head; later calls reuse it
-    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
-      return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta)
-                 : launch_bwd_delta_bf16(ctx, o, dO, lse, delta, lse2, stat3);
-    }));
+  // Row statistic delta_i = dO_i . o_i.  fp32: one prepass for every row and head at the first call, later
+  // calls reuse it.  bf16: the dQ kernel computes it for the rows it owns and stores it (with lse in log2
+  // units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
+  if (f32 && lo == 0) {
+    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] { return launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta); }));
     if (rc != SLIMATTN_OK) return rc;
   }
   const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
@@ -133,7 +132,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     return timed(SLIMATTN_K_DQ, stream, [&] {
       return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
                                      (float*)dQ, items, n)
-                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, lse2, delta, dQ, items, n);
+                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, o, lse, stat3, dQ, items, n);
     });
   };
   auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {
@@ -163,10 +162,10 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   if (whole && !per_unit) {
     // One scope holding every slice: each key tile's owner sums all later query rows itself and
     // writes dK/dV directly; the fp32 accumulators in the workspace are not touched.
-    rc = hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1)
-                    : run_dkdv_split(t->fused, t->d_fused, 0, 0, 1));
+    rc = hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
     if (rc != SLIMATTN_OK) return rc;
-    return hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
+    return hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1)
+                      : run_dkdv_split(t->fused, t->d_fused, 0, 0, 1));
   }
 
   const auto& qoff = t->per_unit[1].q_off[zq];
@@ -183,13 +182,13 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     // Units run one after another on the stream; each adds its queries' contributions to the
     // accumulators of every key tile of the prefix it sees (read-modify-write by the tile's
     // single owner), so the summation order is the unit order.
-    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0)
-                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u, 1, 0));
-    if (rc != SLIMATTN_OK) return rc;
     if (per_unit) {
       rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));
       if (rc != SLIMATTN_OK) return rc;
     }
+    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0)
+                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u, 1, 0));
+    if (rc != SLIMATTN_OK) return rc;
   }
   if (hi == n_units) {
     rc = hip_rc(timed(SLIMATTN_K_FINALIZE, stream, [&] {

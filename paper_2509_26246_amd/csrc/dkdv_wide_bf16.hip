@@ -317,7 +317,9 @@ __device__ __forceinline__ void dkdv_wide_block(
   // A step's statistics for this lane's row (-lse2, -delta as bf16 triples; rows past the end of the run
   // are masked later), through a buffer descriptor: a per-lane byte offset (stat_voff) plus a scalar one.
   const __amdgpu_buffer_rsrc_t stat_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)stat3, 0, (int)((size_t)T * Hq * 16), 0x00020000);
-  auto stat_voff = [&](const Step& d) -> int { return min(d.i0 + l32, T - 1) * 16; };
+  // (a row past the end of the run takes the run's last row: finite numbers of this launch's own scope,
+  // whatever the rest of the array holds; its scores are masked)
+  auto stat_voff = [&](const Step& d) -> int { return min(d.i0 + l32, d.hi - 1) * 16; };
   auto load_stat_at = [&](const Step& d, int voff) -> bf16x8 {
     typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
     return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(stat_rsrc, voff, d.head * T * 16, 0));

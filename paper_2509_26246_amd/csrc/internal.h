@@ -106,11 +106,9 @@ int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
 
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
-int launch_bwd_delta_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, float* delta, float* lse2,
-                          void* stat3);
 // the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
-int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const float* lse2,
-                       const float* delta, void* dQ, const QItem* items, int n_items);
+int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* o,
+                       const float* lse, void* stat3, void* dQ, const QItem* items, int n_items);
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments
 int launch_bwd_dkdv_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,

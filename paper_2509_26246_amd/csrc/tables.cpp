@@ -287,7 +287,7 @@ size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_
     const size_t slots = (size_t)std::max({t->per_unit[0].max_slots[ti][c], t->per_unit[1].max_slots[ti][c], t->fused.max_slots[ti][c]});
     parts = std::max(parts, slots * hkv * 2 * kSplitTileRows[ti] * d * sizeof(float));
   }
-  return align_up(2 * T * hkv * d * sizeof(float)) + 2 * align_up(T * hq * sizeof(float)) + align_up(T * hq * 16) + align_up(parts) + 256;
+  return align_up(2 * T * hkv * d * sizeof(float)) + align_up(T * hq * sizeof(float)) + align_up(T * hq * 16) + align_up(parts) + 256;
 }
 
 }  // extern "C"
