@@ -91,6 +91,8 @@ typedef struct slimattn_params {
 } slimattn_params;
 
 #define SLIMATTN_FLAG_PER_UNIT_LAUNCH 1  /* one launch per unit instead of one fused launch over the range */
+#define SLIMATTN_FLAG_STATS_PREPASS   2  /* bf16 backward: row statistics (delta = dO . O) in a launch of their own instead of
+                                          * inside the dQ kernel (what the library does by itself for very long samples) */
 
 #define SLIMATTN_CHECK_FORWARD   0
 #define SLIMATTN_CHECK_BACKWARD  1

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(HERE, "libslimattn.so")
 
 F32, BF16 = 0, 1
 FLAG_PER_UNIT_LAUNCH = 1
+FLAG_STATS_PREPASS = 2
 CHECK_FORWARD, CHECK_BACKWARD, CHECK_ORDER = 0, 1, 2
 POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "TOKEN_CAP": 4, "SEEDED_LPT": 5,
                 "ISOLATE_FILL": 6}

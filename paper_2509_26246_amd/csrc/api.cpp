@@ -120,10 +120,17 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
 
   // Row statistic delta_i = dO_i . o_i.  fp32: one prepass for every row and head at the first call, later
-  // calls reuse it.  bf16: the dQ kernel computes it for the rows it owns and stores it (with lse in log2
-  // units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
-  if (f32 && lo == 0) {
-    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] { return launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta); }));
+  // calls reuse it.  bf16: normally the dQ kernel computes it for the rows it owns and stores it (with lse in
+  // log2 units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
+  // With a very long sample (its K and V, over all KV heads, far beyond what the caches hold) the dQ blocks
+  // depend on streaming the same K/V tiles at the same time, and the longer prologue cost 9 % there
+  // (256K sample); then a prepass stores the statistics for every row, as in fp32 mode.
+  const bool own_stats = !f32 && !(p->flags & SLIMATTN_FLAG_STATS_PREPASS) &&
+                         (size_t)t->max_sample_len * p->n_kv_heads * p->head_dim * 4 <= (size_t(128) << 20);
+  if (lo == 0 && !own_stats) {
+    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
+      return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta) : launch_bwd_stat_bf16(ctx, o, dO, lse, stat3);
+    }));
     if (rc != SLIMATTN_OK) return rc;
   }
   const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
@@ -132,7 +139,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     return timed(SLIMATTN_K_DQ, stream, [&] {
       return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
                                      (float*)dQ, items, n)
-                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, o, lse, stat3, dQ, items, n);
+                 : launch_bwd_dq_bf16(ctx, q, k, v, dO, o, lse, stat3, own_stats ? 1 : 0, dQ, items, n);
     });
   };
   auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {

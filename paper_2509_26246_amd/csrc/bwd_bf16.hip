@@ -35,6 +35,39 @@ __device__ __forceinline__ void split3(float x, bf16x8& w, int at) {
   w[at + 2] = (bf16)r;
 }
 
+// Two bf16 triples of a row's statistics: -lse2 in elements 0..2, -delta in 4..6.
+__device__ __forceinline__ bf16x8 stat_triples(float lse2, float dlt) {
+  bf16x8 w;
+  split3(-lse2, w, 0);
+  split3(-dlt, w, 4);
+  w[3] = (bf16)0.f;
+  w[7] = (bf16)0.f;
+  return w;
+}
+
+// Prepass: the statistics of every row and head (launches whose dQ kernel does not compute them itself).
+template <int D>
+__global__ __launch_bounds__(256) void stat_bf16_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dO,
+                                                        const float* __restrict__ lse, bf16x8* __restrict__ stat3, int T, int Hq) {
+  constexpr int LPR = D / 8;                                   // lanes per (row, head)
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t rh = idx / LPR;                                // row * Hq + head
+  const bool live = rh < (int64_t)T * Hq;
+  float s = 0.f;
+  if (live) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + idx * 8);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + idx * 8);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s = fmaf((float)a[t], (float)b[t], s);
+  }
+#pragma unroll
+  for (int w = LPR / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w);
+  if (live && (idx % LPR) == 0) {
+    const size_t at = (size_t)(rh % Hq) * T + (rh / Hq);
+    stat3[at] = stat_triples(lse[at] * kLog2e, s);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // One 64-key tile of the dQ walk for this wave's 32 query rows.  MASKED tiles touch the diagonal.
 // pk[ks]: this lane's K-fragment address (key block 0, head-dim step ks) in the current buffer; the
@@ -114,7 +147,7 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
   }
 }
 
-template <int D>
+template <int D, bool OWN_STATS>
 __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                          const bf16* __restrict__ v, const bf16* __restrict__ dO,
                                                          const bf16* __restrict__ o, const float* __restrict__ lse,
@@ -139,33 +172,35 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
   stage_tile<D, kDqBK, 256>(lds, srcK, 0, tid);
   stage_tile<D, kDqBK, 256>(lds + kTileBytes, srcV, 0, tid);
 
-  // The block's Q and dO rows, and on the way the row statistics of the backward pass: delta = dO . O
-  // (the lane's half of the head dim, then the two half-waves that share a row) and lse in log2 units.
-  // Every (row, head) of the launch scope belongs to exactly one dQ block, so this is also where the
-  // statistics are stored for the dK/dV kernel, which runs after this one: -lse2 and -delta as three
-  // bf16 terms each (a product with a fragment of ones adds them into an accumulator exactly).
+  // The block's Q and dO rows and the row statistics of the backward pass: lse in log2 units and delta =
+  // dO . O.  OWN_STATS: computed here (the lane's half of the head dim, then the two half-waves that
+  // share a row) and, as every (row, head) of the launch scope belongs to exactly one dQ block, stored for
+  // the dK/dV kernel, which runs after this one: -lse2 and -delta as three bf16 terms each (a product
+  // with a fragment of ones adds them into an accumulator exactly).  Otherwise a prepass has stored them
+  // and the triples are added up again.
   bf16x8 qf[NKS], dof[NKS];
-  float dlt = 0.f;
+  float dlt = 0.f, lse2;
   {
     const size_t off = ((size_t)ld_row * Hq + h) * D + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       qf[ks] = scale8(*reinterpret_cast<const bf16x8*>(q + off + 16 * ks), scale * kLog2e);
       dof[ks] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * ks);
-      const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + 16 * ks);
+      if constexpr (OWN_STATS) {
+        const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + 16 * ks);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dlt = fmaf((float)of[e], (float)dof[ks][e], dlt);
+        for (int e = 0; e < 8; ++e) dlt = fmaf((float)of[e], (float)dof[ks][e], dlt);
+      }
     }
   }
-  dlt += xor32(dlt);
-  const float lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
-  if (half == 0 && my_row < q_end) {
-    bf16x8 w;
-    split3(-lse2, w, 0);
-    split3(-dlt, w, 4);
-    w[3] = (bf16)0.f;
-    w[7] = (bf16)0.f;
-    stat3[(size_t)h * T + my_row] = w;
+  if constexpr (OWN_STATS) {
+    dlt += xor32(dlt);
+    lse2 = lse[(size_t)h * T + ld_row] * kLog2e;
+    if (half == 0 && my_row < q_end) stat3[(size_t)h * T + my_row] = stat_triples(lse2, dlt);
+  } else {
+    const bf16x8 w = stat3[(size_t)h * T + ld_row];
+    lse2 = -(((float)w[0] + (float)w[1]) + (float)w[2]);
+    dlt = -(((float)w[4] + (float)w[5]) + (float)w[6]);
   }
   lds_cptr pk[NKS], pkt[NDB][2];
 #pragma unroll
@@ -263,22 +298,44 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
 int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kSplitTileRows[0]; }   // bf16: the dK/dV kernel's 256 key rows per block
 
+int launch_bwd_stat_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, void* stat3) {
+  const slimattn_params& p = *c.p;
+  const int64_t n = c.T * p.n_q_heads * (p.head_dim / 8);
+  if (n == 0) return 0;
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL(stat_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse,
+                       (bf16x8*)stat3, (int)c.T, p.n_q_heads);
+  else
+    hipLaunchKernelGGL(stat_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse,
+                       (bf16x8*)stat3, (int)c.T, p.n_q_heads);
+  return (int)hipGetLastError();
+}
+
+namespace {
+template <int D, bool OWN>
+void launch_dq(const LaunchCtx& c, dim3 grid, dim3 block, const void* q, const void* k, const void* v, const void* dO, const void* o,
+               const float* lse, void* stat3, void* dQ, const QItem* items, int n_items) {
+  const slimattn_params& p = *c.p;
+  hipLaunchKernelGGL((dq_bf16_kernel<D, OWN>), grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
+                     (const bf16*)v, (const bf16*)dO, (const bf16*)o, lse, (bf16x8*)stat3, (bf16*)dQ, items, n_items, (int)c.T,
+                     p.n_q_heads, p.n_kv_heads, p.scale);
+}
+}  // namespace
+
 int launch_bwd_dq_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const void* o,
-                       const float* lse, void* stat3, void* dQ, const QItem* items, int n_items) {
+                       const float* lse, void* stat3, int own_stats, void* dQ, const QItem* items, int n_items) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const int g = p.n_q_heads / p.n_kv_heads;
   const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g)), block(256);
-  if (p.head_dim == 128)
-    hipLaunchKernelGGL(dq_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (const bf16*)dO, (const bf16*)o, lse, (bf16x8*)stat3, (bf16*)dQ, items, n_items, (int)c.T,
-                       p.n_q_heads,
-                       p.n_kv_heads, p.scale);
-  else
-    hipLaunchKernelGGL(dq_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (const bf16*)dO, (const bf16*)o, lse, (bf16x8*)stat3, (bf16*)dQ, items, n_items, (int)c.T,
-                       p.n_q_heads,
-                       p.n_kv_heads, p.scale);
+  if (p.head_dim == 128) {
+    if (own_stats) launch_dq<128, true>(c, grid, block, q, k, v, dO, o, lse, stat3, dQ, items, n_items);
+    else launch_dq<128, false>(c, grid, block, q, k, v, dO, o, lse, stat3, dQ, items, n_items);
+  } else {
+    if (own_stats) launch_dq<64, true>(c, grid, block, q, k, v, dO, o, lse, stat3, dQ, items, n_items);
+    else launch_dq<64, false>(c, grid, block, q, k, v, dO, o, lse, stat3, dQ, items, n_items);
+  }
   return (int)hipGetLastError();
 }
 

@@ -72,6 +72,7 @@ struct DeviceLists {                            // device mirrors (pointers into
 struct slimattn_tables {
   int32_t n_samples = 0, n_slices = 0, n_units[2] = {0, 0};
   int64_t total_tokens = 0;
+  int32_t max_sample_len = 0;
   std::vector<int32_t> cu;
   std::vector<slimattn_slice> slices;
   std::vector<int32_t> unit_ptr[2], unit_slices[2];      // [0] forward list, [1] backward list
@@ -107,8 +108,12 @@ int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
 // the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
+// Row statistics of the bf16 backward (-lse*log2e and -delta = -dO.O per row and head, as bf16 triples):
+// either the dQ kernel computes and stores them for the rows it owns (own_stats != 0; `o`, `lse` read), or
+// the prepass below has stored them for every row and the dQ kernel reads them (own_stats == 0).
+int launch_bwd_stat_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, void* stat3);
 int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* o,
-                       const float* lse, void* stat3, void* dQ, const QItem* items, int n_items);
+                       const float* lse, void* stat3, int own_stats, void* dQ, const QItem* items, int n_items);
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments
 int launch_bwd_dkdv_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,

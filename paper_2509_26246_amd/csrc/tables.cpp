@@ -186,6 +186,7 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     t->n_units[0] = n_fwd_units;
     t->n_units[1] = n_bwd_units;
     t->total_tokens = cu[n];
+    for (int32_t i = 0; i < n; ++i) t->max_sample_len = std::max(t->max_sample_len, cu[i + 1] - cu[i]);
     t->cu.assign(cu, cu + n + 1);
     t->slices.assign(slices, slices + n_slices);
     t->unit_ptr[0].assign(fwd_unit_ptr, fwd_unit_ptr + n_fwd_units + 1);

@@ -64,6 +64,11 @@ def _run_modes(prob, ref, tol_o, tol_g, tag):
     prob.forward(unit_lo=0, unit_hi=cf); prob.forward(unit_lo=cf, unit_hi=nf)
     prob.backward(unit_lo=0, unit_hi=cb); prob.backward(unit_lo=cb, unit_hi=nb); torch.cuda.synchronize()
     _check(prob, ref, tol_o, tol_g, tag + "/split")
+    # the backward's row statistics from a launch of their own (what the library chooses for very long samples)
+    for flags, mode in ((S.FLAG_STATS_PREPASS, "fused"), (S.FLAG_STATS_PREPASS | S.FLAG_PER_UNIT_LAUNCH, "per-unit")):
+        _poison(prob)
+        prob.forward(flags=flags & S.FLAG_PER_UNIT_LAUNCH); prob.backward(flags=flags); torch.cuda.synchronize()
+        _check(prob, ref, tol_o, tol_g, tag + "/stats-prepass/" + mode)
 
 
 def _tables(lengths, slice_size, fwd_pol, bwd_pol):
