@@ -143,48 +143,60 @@ __device__ __forceinline__ void score_products(const lds_cptr (&pq)[kNKS<D>], in
   });
 }
 
-// Element-wise work, P = exp2(S - lse) and dS = P (dP - delta), as a stream of 32 values (value j:
-// key block j / 16, register j % 16) cut into slots, one slot behind each gradient product.  Slot j:
-// the exponential of value j, the dS product of value j - 1, and one packing to bf16: P of the pair
-// (j - 1, j) in odd slots, dS of the pair (j - 2, j - 1) in even ones; the last slot also finishes
-// value 31.  One transcendental and two plain vector instructions: with the product's own issue that
-// fills, and does not exceed, the time the matrix unit spends on one product.  Each slot is one asm
-// statement: the compiler keeps asm statements in program order (as ordinary code it moves the whole
-// stream behind the last product of the loop body, where nothing overlaps it) and puts no wait states
-// between the instructions.  A transcendental result may not be read by the very next vector
-// instruction: the instruction behind each exponential reads other registers.
+// Element-wise work, P = exp2(S - lse) and dS = P (dP - delta), as a stream of 32 values cut into slots,
+// one slot behind each gradient product (two at head dim 64).  Slot j: the exponential of value j, the dS
+// product of value j - 1, and one packing to bf16: P of the pair (j - 1, j) in odd slots, dS of the pair
+// (j - 2, j - 1) in even ones; the last slot also finishes value 31.  One transcendental and two plain
+// vector instructions: with the product's own issue that fills, and does not exceed, the time the matrix
+// unit spends on one product.  Each slot is one asm statement: the compiler keeps asm statements in
+// program order (as ordinary code it moves the whole stream behind the last product of the loop body,
+// where nothing overlaps it) and puts no wait states between the instructions.  A transcendental
+// result may not be read by the very next vector instruction: the instruction behind each
+// exponential reads other registers.
+// Order of the values: the first half of the stream (which runs behind the products of the first 16-row
+// half) holds registers 8..15 of the two key blocks, i.e. the packed fragments of the second 16-row half,
+// which go to the temporaries tp, td; the second half holds registers 0..7, whose fragments go straight
+// into pf[.][0], ds[.][0]: those were last read by the products of the first half.  Only the
+// temporaries are copied at the end of the iteration.
+struct EwValue { int kb, r; };
+constexpr EwValue ew_value(int j) { return j < 16 ? EwValue{j >> 3, 8 + (j & 7)} : EwValue{(j - 16) >> 3, (j - 16) & 7}; }
 template <int J>
-__device__ __forceinline__ void ew_slot(floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2], uintx4 (&nds)[2][2]) {
-  constexpr int kb = J >> 4, r = J & 15;
-  constexpr int k1 = (J - 1) >> 4, r1 = (J - 1) & 15;   // value j - 1
-  constexpr int k2 = (J - 2) >> 4, r2 = (J - 2) & 15;   // value j - 2
-  float e = s[kb][r];
+__device__ __forceinline__ void ew_slot(floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&pf)[2][2], uintx4 (&ds)[2][2],
+                                        uintx4 (&tp)[2], uintx4 (&td)[2]) {
+  constexpr EwValue v0 = ew_value(J), v1 = ew_value(J > 0 ? J - 1 : 0), v2 = ew_value(J > 1 ? J - 2 : 0);
+  auto put_p = [&](EwValue v, unsigned w) {             // the word of the pair that ends at value v
+    if (v.r >= 8) tp[v.kb][(v.r & 7) >> 1] = w; else pf[v.kb][0][(v.r & 7) >> 1] = w;
+  };
+  auto put_ds = [&](EwValue v, unsigned w) {
+    if (v.r >= 8) td[v.kb][(v.r & 7) >> 1] = w; else ds[v.kb][0][(v.r & 7) >> 1] = w;
+  };
+  float e = s[v0.kb][v0.r];
   if constexpr (J == 0) {
     asm volatile("v_exp_f32 %0, %0" : "+v"(e));
-    s[kb][r] = e;
+    s[v0.kb][v0.r] = e;
   } else if constexpr (J & 1) {
-    float m = dp[k1][r1];
+    float m = dp[v1.kb][v1.r];
     unsigned w;
     asm volatile("v_exp_f32 %0, %0\n\tv_mul_f32 %1, %3, %1\n\tv_cvt_pk_bf16_f32 %2, %3, %0"
-                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[k1][r1]));
-    s[kb][r] = e;
-    dp[k1][r1] = m;
-    npf[kb][r >> 3][(r & 7) >> 1] = w;
+                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[v1.kb][v1.r]));
+    s[v0.kb][v0.r] = e;
+    dp[v1.kb][v1.r] = m;
+    put_p(v0, w);
     if constexpr (J == 31) {
-      float m2 = dp[1][15];
+      float m2 = dp[v0.kb][v0.r];
       unsigned w2;
-      asm volatile("v_mul_f32 %0, %2, %0\n\tv_cvt_pk_bf16_f32 %1, %3, %0" : "+v"(m2), "=&v"(w2) : "v"(e), "v"(dp[1][14]));
-      dp[1][15] = m2;
-      nds[1][1][3] = w2;
+      asm volatile("v_mul_f32 %0, %2, %0\n\tv_cvt_pk_bf16_f32 %1, %3, %0" : "+v"(m2), "=&v"(w2) : "v"(e), "v"(dp[v1.kb][v1.r]));
+      dp[v0.kb][v0.r] = m2;
+      put_ds(v0, w2);
     }
   } else {
-    float m = dp[k1][r1];
+    float m = dp[v1.kb][v1.r];
     unsigned w;
     asm volatile("v_exp_f32 %0, %0\n\tv_mul_f32 %1, %3, %1\n\tv_cvt_pk_bf16_f32 %2, %4, %1"
-                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[k1][r1]), "v"(dp[k2][r2]));
-    s[kb][r] = e;
-    dp[k1][r1] = m;
-    nds[k2][r2 >> 3][(r2 & 7) >> 1] = w;
+                 : "+v"(e), "+v"(m), "=&v"(w) : "v"(s[v1.kb][v1.r]), "v"(dp[v2.kb][v2.r]));
+    s[v0.kb][v0.r] = e;
+    dp[v1.kb][v1.r] = m;
+    put_ds(v1, w);
   }
 }
 
@@ -199,20 +211,20 @@ __device__ __forceinline__ void grad_read(const lds_cptr (&pqt)[kNDB<D>][2], Tr2
 // Gradient products of one step, dV_kb^T += dO^T P_kb and dK_kb^T += Q^T dS_kb, with P, dS packed in
 // pf[kb][half16], ds[kb][half16]; pqt[][] point at the step's Q tile.  Per head-dim block and 16-row half
 // one batch of two transposed fragments (dO^T, Q^T), each feeding both key blocks.  The element-wise work
-// of the next step (its scores in s, dp) is spread between the products, one value after each, and its
-// packed results are left in npf, nds.  FIRST: the block's first call, which starts the accumulators.
+// of the next step (its scores in s, dp) is spread between the products (see ew_slot), and its packed
+// results are left in pf[.][0], ds[.][0] (first 16-row half) and tp, td (second half).  FIRST: the block's first call, which starts the accumulators.
 template <int D, bool FIRST>
-__device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB<D>][2], const uintx4 (&pf)[2][2],
-                                                  const uintx4 (&ds)[2][2], floatx16 (&dk)[2][kNDB<D>], floatx16 (&dv)[2][kNDB<D>],
-                                                  floatx16 (&s)[2], floatx16 (&dp)[2], uintx4 (&npf)[2][2],
-                                                  uintx4 (&nds)[2][2], Tr2 (&tb)[kGradBatches<D>]) {
+__device__ __forceinline__ void gradient_products(const lds_cptr (&pqt)[kNDB<D>][2], uintx4 (&pf)[2][2], uintx4 (&ds)[2][2],
+                                                  floatx16 (&dk)[2][kNDB<D>], floatx16 (&dv)[2][kNDB<D>], floatx16 (&s)[2],
+                                                  floatx16 (&dp)[2], uintx4 (&tp)[2], uintx4 (&td)[2],
+                                                  Tr2 (&tb)[kGradBatches<D>]) {
   // batch b: head-dim block b % 4 of 16-row half b / 4 (first half first: its P, dS die early); its
   // four reads are issued one behind each product of batch b - 2, those of batches 0 and 1 behind the
   // last score products (by the caller)
   constexpr int kPer = 32 / (4 * kGradBatches<D>);       // element-wise values per product slot (1 at d 128, 2 at d 64)
   auto ew = [&](auto qc) {                              // the element-wise work behind product q of the phase
     constexpr int q = decltype(qc)::value;
-    static_for<0, kPer>([&](auto ec) { ew_slot<kPer * q + decltype(ec)::value>(s, dp, npf, nds); });
+    static_for<0, kPer>([&](auto ec) { ew_slot<kPer * q + decltype(ec)::value>(s, dp, pf, ds, tp, td); });
   };
   static_for<0, kGradBatches<D>>([&](auto ic) {
     constexpr int b = decltype(ic)::value, st = b / kNDB<D>, db = b % kNDB<D>;
@@ -437,14 +449,12 @@ __device__ __forceinline__ void dkdv_wide_block(
       if constexpr (k == kSlotGrad + 7) v_rel -= dq_;
     };
     floatx16 s[2], dp[2];
-    uintx4 npf[2][2], nds[2][2];
+    uintx4 tp[2], td[2];                                // packed P, dS of the second 16-row half of the step being scored
     const int rel_lo[2] = {m_s.rel_lo0, m_s.rel_lo0 + 32};
     score_products<D>(pq, v_rel, stat_s, ones_l, ones_d, kf, s, dp, m_s.masked, rel_lo, m_s.rel_hi, between);
-    gradient_products<D, first>(pqt, pf, ds, dk, dv, s, dp, npf, nds, tb);
+    gradient_products<D, first>(pqt, pf, ds, dk, dv, s, dp, tp, td, tb);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) { pf[kb][h2] = npf[kb][h2]; ds[kb][h2] = nds[kb][h2]; }
+    for (int kb = 0; kb < 2; ++kb) { pf[kb][1] = tp[kb]; ds[kb][1] = td[kb]; }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     again = have_s;
