@@ -104,7 +104,8 @@ def test_fp32_gqa_and_head_dims(hq, hkv, d):
     _run_modes(prob, ref, TOL_F32, TOL_F32, f"f32 {hq}/{hkv}/{d}")
 
 
-@pytest.mark.parametrize("hq,hkv,d,slice_size", [(4, 2, 128, 64), (2, 1, 64, 64), (8, 2, 128, 192), (4, 4, 64, 1000)])
+@pytest.mark.parametrize("hq,hkv,d,slice_size", [(4, 2, 128, 64), (2, 1, 64, 64), (8, 2, 128, 192), (4, 4, 64, 1000),
+                                                   (8, 1, 128, 256), (8, 1, 64, 500), (3, 1, 128, 128), (6, 2, 64, 96)])
 def test_bf16_small_packs_full_oracle(hq, hkv, d, slice_size):
     L = [37, 128, 200, 511, 1, 1000, 0, 129]
     cu, sl, fu, bu = _tables(L, slice_size, ("PREFIX_FILL", {"m": 4, "w_quad": 2, "w_lin": 0}),
