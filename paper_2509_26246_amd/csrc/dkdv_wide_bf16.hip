@@ -333,7 +333,6 @@ __device__ __forceinline__ void dkdv_wide_block(
   // whatever the rest of the array holds; its scores are masked)
   auto stat_voff = [&](const Step& d) -> int { return min(d.i0 + l32, d.hi - 1) * 16; };
   auto load_stat_at = [&](const Step& d, int voff) -> bf16x8 {
-    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
     return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(stat_rsrc, voff, d.head * T * 16, 0));
   };
   auto load_stat = [&](const Step& d) -> bf16x8 { return load_stat_at(d, stat_voff(d)); };
