@@ -176,8 +176,10 @@ def test_bf16_divided_key_tiles(hq, hkv, d):
             assert np.array_equal(x, y), "dK/dV differ between two identical runs"
 
 
-def test_cfg1_full_size_sampled_rows_and_identities():
-    w = W.WORKLOADS["cfg1_llama8b_32k"]
+@pytest.mark.parametrize("name", ["cfg1_llama8b_32k", "cfg2_tp8_70b_128k", "cfg4_d64_s4096"])
+def test_full_size_sampled_rows_and_identities(name):
+    # the bench workload, a TP share with one KV head and a 128K sample (divided key tiles), and a head-dim-64 pack
+    w = W.WORKLOADS[name]
     rng = np.random.default_rng(1)
     L = W.draw_lengths(w, rng)
     T_ = int(L.sum())
