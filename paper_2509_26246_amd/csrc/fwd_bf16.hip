@@ -503,6 +503,9 @@ int launch_fwd_bf16(const LaunchCtx& c, const void* q, const void* k, const void
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const int g = p.n_q_heads / p.n_kv_heads;
+#ifndef SLIMATTN_FWD_PAIR
+  if (g % 2 == 0 && p.head_dim == 128) return launch_fwd_wide_bf16(c, q, k, v, o, lse, items, n_items);
+#endif
   if (g % 2 == 0) {
     const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g / 2)), block(512);
     if (p.head_dim == 128)

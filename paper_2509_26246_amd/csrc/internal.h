@@ -107,6 +107,9 @@ int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
 
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
+// even group sizes at head dim 128: one wave per SIMD, two heads per wave (fwd_wide_bf16.hip); same arguments
+int launch_fwd_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
+                         const QItem* items, int n_items);
 // the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
 // Row statistics of the bf16 backward (-lse*log2e and -delta = -dO.O per row and head, as bf16 triples):
 // either the dQ kernel computes and stores them for the rows it owns (own_stats != 0; `o`, `lse` read), or
