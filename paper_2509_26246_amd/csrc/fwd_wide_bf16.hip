@@ -439,6 +439,8 @@ int launch_fwd_wide_bf16(const LaunchCtx& c, const void* q, const void* k, const
   const slimattn_params& p = *c.p;
   const int g = p.n_q_heads / p.n_kv_heads;
   const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g / 2)), block(256);
+  // (the body also instantiates at head dim 64, where it is bound by the vector unit and no faster than the
+  // two-wave kernel: 1033 against 1027 TFLOP/s on a 16K sample; not dispatched)
   hipLaunchKernelGGL(fwd_wide_bf16_kernel_d128, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                      (const bf16*)v, (bf16*)o, lse, items, n_items, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale);
   return (int)hipGetLastError();

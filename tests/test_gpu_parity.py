@@ -176,6 +176,38 @@ def test_bf16_divided_key_tiles(hq, hkv, d):
             assert np.array_equal(x, y), "dK/dV differ between two identical runs"
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (2, 1, 64), (3, 1, 128)])
+@pytest.mark.parametrize("jump", [6.0, 40.0, 200.0])
+def test_bf16_forward_reference_moves(hq, hkv, d, jump):
+    """Scores that climb far above a row's score against the sample's first key (by `jump` in natural
+    units at one key position, beyond fp32's exponent range for the largest): kernels that take the
+    exponentials against a running reference have to move it, whichever way they choose it.  One
+    feature carries the climb, so the bf16 rounding of the scaled queries is a common factor."""
+    L = [300, 64, 1, 190]
+    T_ = sum(L)
+    q, k, v, dO = _draw(T_, hq, hkv, d, 17, True, qs=0.5, dos=0.1)
+    scale = d ** -0.5
+    a = np.float32(4.0)
+    b = np.float32(jump / (2 * 4.0 * scale))            # q0 * k0 * scale = +-jump / 2
+    q[:, :, 0] = a
+    st = 0
+    for l in L:
+        k[st:st + l, :, 0] = -b                         # the first keys of a sample score low ...
+        k[st + min(l - 1, 70):st + l, :, 0] = b         # ... later ones high
+        st += l
+    q, k = W.bf16_round(q), W.bf16_round(k)
+    cu, sl, fu, bu = _tables(L, 128, ("ALL", {}), ("ALL", {}))
+    o, lse = A.fwd_packed(q, k, v, cu, scale)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    _poison(prob)
+    prob.forward(); torch.cuda.synchronize()
+    got_o, got_lse = H.device_to_f32(prob.o), prob.lse.cpu().numpy()
+    assert np.isfinite(got_o).all() and np.isfinite(got_lse).all()
+    assert float(np.max(np.abs(got_o - o))) <= TOL_O
+    # lse carries the score's own rounding (|score| * 2^-9 from the bf16 scaled query): relative bound
+    assert float(np.max(np.abs(got_lse - lse) / (1.0 + np.abs(lse)))) <= TOL_O
+
+
 @pytest.mark.parametrize("name", ["cfg1_llama8b_32k", "cfg2_tp8_70b_128k", "cfg4_d64_s4096"])
 def test_full_size_sampled_rows_and_identities(name):
     # the bench workload, a TP share with one KV head and a 128K sample (divided key tiles), and a head-dim-64 pack
