@@ -16,7 +16,8 @@
 // packed probabilities, one per slot:
 //   iteration t:  [S(t+1, kb 0) | EW(t, kb 1) first half]   [PV(t, kb 0) | EW(t, kb 1) second half]
 //                 [S(t+1, kb 1) | EW(t+1, kb 0) first half] [PV(t, kb 1) | EW(t+1, kb 0) second half]  barrier
-// K(t+2) and V(t+1) are staged global -> LDS during iteration t into the buffers iteration t-1 read.
+// K(t+2) and V(t+1) are staged global -> LDS during iteration t into the buffers iteration t-1 read (the first
+// iteration, which has no tile before it, stages nothing: K(0), K(1), V(0) come with the item's first loads).
 //
 // Softmax reference.  A row's reference m is its score against the sample's first key (every row sees it),
 // computed in the prologue; the first product of a score accumulator takes -m as its C operand from a
@@ -133,16 +134,13 @@ __device__ __forceinline__ void ew_flush(uintx4 (&pf)[2][2][2], float& e0, float
 }
 
 template <int D>
-__device__ __forceinline__ void fwd_wide_block(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                                               bf16* __restrict__ o_out, float* __restrict__ lse, const QItem* __restrict__ items,
-                                               int n_items, int T, int Hq, int Hkv, float scale) {
+__device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, const int hp, const bf16* __restrict__ q,
+                                              const bf16* __restrict__ k, const bf16* __restrict__ v, bf16* __restrict__ o_out,
+                                              float* __restrict__ lse, int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = kNKS<D>, NDB = kNDB<D>, NVF = kNVF<D>, PER = kPer<D>;
   __shared__ __attribute__((aligned(1024))) char smem[4 * kTileBytes<D>];
 
   const int g = Hq / Hkv;
-  int item_idx, hk, hp;
-  if (!map_block(blockIdx.x, g >> 1, Hkv, n_items, &item_idx, &hk, &hp)) return;
-  const QItem it = items[item_idx];
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int h0 = hk * g + 2 * hp;
   const int q0w = it.q_row0 + 32 * wave, my_row = q0w + l32, q_end = it.q_row0 + it.q_rows;
@@ -166,7 +164,10 @@ __device__ __forceinline__ void fwd_wide_block(const bf16* __restrict__ q, const
   }
   const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
   const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  // K(0), K(1) and V(0) are on their way before anything waits: one memory latency per item, not one per early tile
   stage_tile<D, kKeys, 256>(lds, srcK, 0, tid);
+  stage_tile<D, kKeys, 256>(lds + kTileBytes<D>, srcK, kKeys, tid);
+  stage_tile<D, kKeys, 256>(lds + kVBase<D>, srcV, 0, tid);
 
   lds_cptr pk[NKS], pv[NDB][2];                         // fragment addresses: K buffer 0, V buffer 0
 #pragma unroll
@@ -351,7 +352,7 @@ __device__ __forceinline__ void fwd_wide_block(const bf16* __restrict__ q, const
     auto extra_a0 = [&](auto pc) {                      // V pointers to this iteration's buffer; K(t+2) staged
       constexpr int p = decltype(pc)::value;
       if constexpr (p < 2 * NDB) lds_ptr_add(pv[p / 2][p % 2], dbuf);
-      if constexpr (p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
+      if constexpr (!first && p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
         constexpr int pass = (p - 2 * NDB) / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(srcK.rsrc, lds + kdst + pass * 4096, 16, srcK.voff,
                                                  ksoff + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
@@ -359,7 +360,7 @@ __device__ __forceinline__ void fwd_wide_block(const bf16* __restrict__ q, const
     };
     auto extra_a1 = [&](auto pc) {                      // V(t+1) staged
       constexpr int p = decltype(pc)::value;
-      if constexpr (p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
+      if constexpr (!first && p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
         constexpr int pass = (p - 2 * NDB) / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(srcV.rsrc, lds + vdst + pass * 4096, 16, srcV.voff,
                                                  ksoff - kKeys * srcK.row_bytes + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
@@ -424,11 +425,51 @@ __device__ __forceinline__ void fwd_wide_block(const bf16* __restrict__ q, const
   }
 }
 
+// A block walks the work list in rounds of the grid's size (the launch has as many blocks as the chip holds at
+// one per compute unit, a multiple of 8, so a block stays with one residue of the block -> item mapping, i.e.
+// with the K/V streams of its XCD).
+// The next item's descriptor is fetched while the current item runs -- with a vector load: a scalar load
+// in flight would make the hand-counted LDS waits of the tile loop unreliable -- so that an item starts with
+// its own loads instead of a chain of dependent ones.
+template <int D>
+__device__ __forceinline__ void fwd_wide_walk(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                                              bf16* __restrict__ o, float* __restrict__ lse, const QItem* __restrict__ items,
+                                              int n_items, int T, int Hq, int Hkv, float scale) {
+  const int g2 = (Hq / Hkv) >> 1;
+  const int total = ((n_items * Hkv + 7) / 8) * 8 * g2;   // block numbers of the mapping, padding included
+  const __amdgpu_buffer_rsrc_t irsrc = __builtin_amdgcn_make_buffer_rsrc((void*)items, 0, n_items * (int)sizeof(QItem), 0x00020000);
+  typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
+  auto fetch = [&](int b, int* hk, int* hp) -> intx4 {  // block number -> descriptor (zero rows for padding numbers)
+    int idx = 0;
+    const bool ok = b < total && map_block(b, g2, Hkv, n_items, &idx, hk, hp);
+    const intx4 z = {0, 0, 0, 0};
+    return ok ? __builtin_bit_cast(intx4, __builtin_amdgcn_raw_buffer_load_b128(irsrc, 0, idx * (int)sizeof(QItem), 0)) : z;
+  };
+  // round k takes the numbers k G .. k G + G - 1; within its residue class a block goes up the list in even
+  // rounds and down in odd ones, which evens out the shares of a list sorted by weight
+  const int G = gridDim.x, r8 = blockIdx.x & 7, j8 = blockIdx.x >> 3;
+  auto number = [&](int round) -> int { return round * G + ((round & 1) ? 8 * ((G >> 3) - 1 - j8) + r8 : 8 * j8 + r8); };
+  int hk = 0, hp = 0, hk_n = 0, hp_n = 0;
+  intx4 cur = fetch(number(0), &hk, &hp);
+  for (int round = 0; round * G < total; ++round) {
+    const intx4 nxt = fetch(number(round + 1), &hk_n, &hp_n);
+    QItem it;
+    it.q_row0 = __builtin_amdgcn_readfirstlane(cur[0]);
+    it.q_rows = __builtin_amdgcn_readfirstlane(cur[1]);
+    it.kv_start = __builtin_amdgcn_readfirstlane(cur[2]);
+    it.pad = 0;
+    if (it.q_rows > 0) fwd_wide_item<D>(it, hk, hp, q, k, v, o, lse, T, Hq, Hkv, scale);
+    cur = nxt;
+    hk = hk_n;
+    hp = hp_n;
+  }
+}
+
 __global__ __launch_bounds__(256, 1) void fwd_wide_bf16_kernel_d128(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                                      const bf16* __restrict__ v, bf16* __restrict__ o,
                                                                      float* __restrict__ lse, const QItem* __restrict__ items,
                                                                      int n_items, int T, int Hq, int Hkv, float scale) {
-  fwd_wide_block<128>(q, k, v, o, lse, items, n_items, T, Hq, Hkv, scale);
+  fwd_wide_walk<128>(q, k, v, o, lse, items, n_items, T, Hq, Hkv, scale);
 }
 
 }  // namespace
@@ -438,7 +479,15 @@ int launch_fwd_wide_bf16(const LaunchCtx& c, const void* q, const void* k, const
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const int g = p.n_q_heads / p.n_kv_heads;
-  const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g / 2)), block(256);
+  // one block per compute unit is resident (512 registers per lane); the device's count, rounded to the mapping's 8
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    n_cu = (v + 7) / 8 * 8;
+  }
+  const int total = mapped_grid(n_items, p.n_kv_heads, g / 2);
+  const dim3 grid(total < n_cu ? total : n_cu), block(256);
   // (the body also instantiates at head dim 64, where it is bound by the vector unit and no faster than the
   // two-wave kernel: 1033 against 1027 TFLOP/s on a 16K sample; not dispatched)
   hipLaunchKernelGGL(fwd_wide_bf16_kernel_d128, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
