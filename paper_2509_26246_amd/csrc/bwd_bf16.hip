@@ -75,21 +75,21 @@ __global__ __launch_bounds__(256) void stat_bf16_kernel(const bf16* __restrict__
 template <int D, bool MASKED>
 __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_cptr (&pkt)[D / 32][2],
                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], floatx16 (&acc)[D / 32],
-                                        float lse2, float dlt, int rel) {
+                                        const floatx16& negl, const floatx16& negd, int rel) {
   constexpr int NKS = D / 16, NDB = D / 32, kRowBytes = D * 2, kTileBytes = kDqBK * D * 2;
   bf16x8 dsf[4];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     floatx16 sc, dpc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { sc[r] = -lse2; dpc[r] = 0.f; }
-    // S^T = K Q^T - lse (log2 units: qf holds q * scale * log2 e) and dP^T = V dO^T for 32 keys:
-    // K and V fragments alternate in one stream
+    // S^T = K Q^T - lse (log2 units: qf holds q * scale * log2 e) and dP^T = V dO^T - delta for 32 keys: K and V
+    // fragments alternate in one stream.  The first product of each accumulator takes its C operand from a
+    // register block that holds -lse (-delta) of the lane's row in every register: nothing is initialised and
+    // the element-wise part has no subtraction.
     frag_pipeline<2 * NKS, 4, 1, 1>(
         [&](int i) { return lds_ld_row(pk[i >> 1], b * 32 * kRowBytes + (i & 1) * kTileBytes); },
         [&](int i, bf16x8 f) {
-          if (i & 1) dpc = mfma32(f, dof[i >> 1], dpc);
-          else sc = mfma32(f, qf[i >> 1], sc);
+          if (i & 1) dpc = mfma32(f, dof[i >> 1], i == 1 ? negd : dpc);
+          else sc = mfma32(f, qf[i >> 1], i == 0 ? negl : sc);
         });
     // the element-wise part runs at raised priority: a wave that streams products would otherwise
     // keep the vector issue port and starve the other wave's softmax
@@ -97,7 +97,7 @@ __device__ __forceinline__ void dq_tile(const lds_cptr (&pk)[D / 16], const lds_
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float p = __builtin_amdgcn_exp2f(sc[r]);
-      const float ds = p * (dpc[r] - dlt);
+      const float ds = p * dpc[r];
       sc[r] = (MASKED && 32 * b + 8 * (r >> 2) + (r & 3) > rel) ? 0.f : ds;   // key > row contributes nothing
     }
     dsf[2 * b] = pack8(sc, 0);
@@ -202,6 +202,10 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
     lse2 = -(((float)w[0] + (float)w[1]) + (float)w[2]);
     dlt = -(((float)w[4] + (float)w[5]) + (float)w[6]);
   }
+  floatx16 negl, negd;                                  // the C operands of every tile's first products
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { negl[r] = -lse2; negd[r] = -dlt; }
+  asm volatile("" : "+v"(negl), "+v"(negd));            // kept in registers, not rebuilt at every use
   lds_cptr pk[NKS], pkt[NDB][2];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) pk[ks] = lds_row_ptr<D>(lds, l32, 16 * ks + 8 * half);
@@ -225,9 +229,9 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
     stage_tile<D, kDqBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kDqBK, tid);
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kDqBK - 1 <= q0w) {
-      dq_tile<D, false>(pk, pkt, qf, dof, acc, lse2, dlt, rel);
+      dq_tile<D, false>(pk, pkt, qf, dof, acc, negl, negd, rel);
     } else if (j0 <= q0w + 31) {
-      dq_tile<D, true>(pk, pkt, qf, dof, acc, lse2, dlt, rel);
+      dq_tile<D, true>(pk, pkt, qf, dof, acc, negl, negd, rel);
     }
     const int flip = (t & 1) ? -kBufBytes : kBufBytes;   // fragment addresses follow the buffer switch
 #pragma unroll
