@@ -138,7 +138,9 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
                                               const bf16* __restrict__ k, const bf16* __restrict__ v, bf16* __restrict__ o_out,
                                               float* __restrict__ lse, int T, int Hq, int Hkv, float scale) {
   constexpr int NKS = kNKS<D>, NDB = kNDB<D>, NVF = kNVF<D>, PER = kPer<D>;
-  __shared__ __attribute__((aligned(1024))) char smem[4 * kTileBytes<D>];
+  // K and V buffers, then one transposition area per wave for the output rows (row stride padded by 16 bytes)
+  constexpr int kOutStride = kRowBytes<D> + 16, kOutBytes = 32 * kOutStride;
+  __shared__ __attribute__((aligned(1024))) char smem[4 * kTileBytes<D> + 4 * kOutBytes];
 
   const int g = Hq / Hkv;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5, l32 = lane & 31;
@@ -403,24 +405,33 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
   while (t < n_tiles) iteration(IC<0>{}, IC<1>{});
   settle();
 
+  // O = O^T / l, through the wave's own LDS area: a lane owns a row's values in pieces of 4 columns, and written as
+  // they stand each store instruction would touch 32 rows with 16 bytes each; transposed, a store instruction
+  // writes four whole rows.
+  LDS_PTR(char) ep = lds + 4 * kTileBytes<D> + wave * kOutBytes;
+  constexpr int kChunks = kRowBytes<D> / 16, kRowsPerStore = 64 / kChunks;   // 16-byte chunks per row; rows per store
+  const int st_row = lane / kChunks, st_chunk = lane % kChunks;
 #pragma unroll
   for (int hb = 0; hb < 2; ++hb) {
     const float l_run = lr[hb] + lu[hb];
     const float l_tot = l_run + xor32(l_run);
-    if (my_row < q_end) {
-      const int h = h0 + hb;
-      const float inv = 1.f / l_tot;
-      bf16* op = o_out + ((size_t)my_row * Hq + h) * D;
+    const float inv = 1.f / l_tot;
+    const int h = h0 + hb;
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          bf16x4 w;
+      for (int gq = 0; gq < 4; ++gq) {
+        bf16x4 w;
 #pragma unroll
-          for (int x = 0; x < 4; ++x) w[x] = (bf16)(o[hb][db][4 * gq + x] * inv);
-          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq + 4 * half) = w;
-        }
-      if (half == 0) lse[(size_t)h * T + my_row] = (m_ref[hb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        for (int x = 0; x < 4; ++x) w[x] = (bf16)(o[hb][db][4 * gq + x] * inv);
+        *reinterpret_cast<LDS_PTR(bf16x4)>(ep + l32 * kOutStride + (32 * db + 8 * gq + 4 * half) * 2) = w;
+      }
+    if (half == 0 && my_row < q_end) lse[(size_t)h * T + my_row] = (m_ref[hb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+#pragma unroll
+    for (int j = 0; j < 32 / kRowsPerStore; ++j) {
+      const int r = j * kRowsPerStore + st_row;
+      const bf16x8 w = *reinterpret_cast<LDS_PTR(const bf16x8)>(ep + r * kOutStride + st_chunk * 16);
+      if (q0w + r < q_end) *reinterpret_cast<bf16x8*>(o_out + ((size_t)(q0w + r) * Hq + h) * D + st_chunk * 8) = w;
     }
   }
 }
