@@ -241,17 +241,27 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
     __builtin_amdgcn_s_waitcnt(0);                 // this thread's direct loads have landed
     __syncthreads();
   }
-  if (my_row < q_end) {
-    bf16* out = dQ + ((size_t)my_row * Hq + h) * D;
+  // dQ rows out through LDS (the tile buffers are free behind the loop's last barrier; each wave uses a part of
+  // its own): a lane owns a row's values in pieces of 4 columns, and written as they stand each store instruction
+  // would touch 32 rows with 16 bytes each; transposed, a store instruction writes whole rows.
+  constexpr int kOutStride = D * 2 + 16, kChunks = D * 2 / 16, kRowsPerStore = 64 / kChunks;
+  static_assert(4 * 32 * kOutStride <= 2 * kBufBytes, "the transposition areas must fit the tile buffers");
+  LDS_PTR(char) ep = lds + (tid >> 6) * 32 * kOutStride;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+  for (int db = 0; db < NDB; ++db)
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        bf16x4 w;
+    for (int gq = 0; gq < 4; ++gq) {
+      bf16x4 w;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) w[x] = (bf16)(acc[db][4 * gq + x] * scale);
-        *reinterpret_cast<bf16x4*>(out + 32 * db + 8 * gq + 4 * half) = w;
-      }
+      for (int x = 0; x < 4; ++x) w[x] = (bf16)(acc[db][4 * gq + x] * scale);
+      *reinterpret_cast<LDS_PTR(bf16x4)>(ep + l32 * kOutStride + (32 * db + 8 * gq + 4 * half) * 2) = w;
+    }
+  const int st_row = lane / kChunks, st_chunk = lane % kChunks;
+#pragma unroll
+  for (int j = 0; j < 32 / kRowsPerStore; ++j) {
+    const int r = j * kRowsPerStore + st_row;
+    const bf16x8 w = *reinterpret_cast<LDS_PTR(const bf16x8)>(ep + r * kOutStride + st_chunk * 16);
+    if (q0w + r < q_end) *reinterpret_cast<bf16x8*>(dQ + ((size_t)(q0w + r) * Hq + h) * D + st_chunk * 8) = w;
   }
 }
 
