@@ -1,4 +1,6 @@
-// Forward, bf16 inputs, MFMA products with fp32 accumulation, fp32 online softmax.
+// Forward, bf16 inputs, MFMA products with fp32 accumulation, fp32 online softmax: the kernels with two waves
+// per SIMD (head dim 64, and odd numbers of query heads per KV head; even groups at head dim 128 run the
+// one-wave kernel of fwd_wide_bf16.hip).
 //
 // What it computes (paper: PackFlow section -- a slice's queries attend to the cached keys and
 // values of every earlier slice of the sample and causally to the slice itself): for a query tile
@@ -503,9 +505,7 @@ int launch_fwd_bf16(const LaunchCtx& c, const void* q, const void* k, const void
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const int g = p.n_q_heads / p.n_kv_heads;
-#ifndef SLIMATTN_FWD_PAIR
   if (g % 2 == 0 && p.head_dim == 128) return launch_fwd_wide_bf16(c, q, k, v, o, lse, items, n_items);
-#endif
   if (g % 2 == 0) {
     const dim3 grid(mapped_grid(n_items, p.n_kv_heads, g / 2)), block(512);
     if (p.head_dim == 128)
