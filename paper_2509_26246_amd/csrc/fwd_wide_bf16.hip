@@ -198,7 +198,10 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
     for (int u = 0; u < NKS; ++u) {
       qf[hb][u] = scale8(qf[hb][u], scale * kLog2e);
 #pragma unroll
-      for (int x = 0; x < 8; ++x) acc = fmaf((float)qf[hb][u][x], (float)k0[u][x], acc);
+      for (int x = 0; x < 4; ++x) {                     // packed bf16 pairs, fp32 sum (no product runs yet: see ew_slot)
+        const bf16x2 a2 = {qf[hb][u][2 * x], qf[hb][u][2 * x + 1]}, b2 = {k0[u][2 * x], k0[u][2 * x + 1]};
+        acc = __builtin_amdgcn_fdot2_f32_bf16(a2, b2, acc, false);
+      }
     }
     m_ref[hb] = acc + xor32(acc);
 #pragma unroll
