@@ -189,7 +189,10 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
       if constexpr (OWN_STATS) {
         const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + 16 * ks);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dlt = fmaf((float)of[e], (float)dof[ks][e], dlt);
+        for (int e = 0; e < 4; ++e) {                   // packed bf16 pairs, fp32 sum
+          const bf16x2 a2 = {of[2 * e], of[2 * e + 1]}, b2 = {dof[ks][2 * e], dof[ks][2 * e + 1]};
+          dlt = __builtin_amdgcn_fdot2_f32_bf16(a2, b2, dlt, false);
+        }
       }
     }
   }
