@@ -470,6 +470,38 @@ __device__ __forceinline__ void dkdv_wide_block(
   // compiler does not know that the asm statements are matrix products): explicit wait states
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
 
+  if (it.slot < 0 && store_final && !load_acc) {
+    // The fused launch's case: bf16 rows of dK, then of dV, out through LDS (stages and V tile are free behind
+    // the loop's last barrier; each wave uses a part of its own).  A lane owns a row's values in pieces of 4
+    // columns, and written as they stand each store instruction would touch 32 rows with 16 bytes each;
+    // transposed, a store instruction writes whole rows.
+    constexpr int kOutStride = kRowBytes<D> + 16, kChunks = kRowBytes<D> / 16, kRowsPerStore = 64 / kChunks;
+    static_assert(4 * 64 * kOutStride <= kVBase<D> + kVBytes<D>, "the transposition areas must fit the block's LDS");
+    LDS_PTR(char) ep = lds + wave * 64 * kOutStride;
+    const int st_row = lane / kChunks, st_chunk = lane % kChunks;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int db = 0; db < kNDB<D>; ++db)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            bf16x4 w;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) w[x] = which ? (bf16)dv[kb][db][4 * gq + x] : (bf16)(dk[kb][db][4 * gq + x] * scale);
+            *reinterpret_cast<LDS_PTR(bf16x4)>(ep + (32 * kb + l32) * kOutStride + (32 * db + 8 * gq + 4 * half) * 2) = w;
+          }
+      bf16* out = which ? dV : dK;
+#pragma unroll
+      for (int j = 0; j < 64 / kRowsPerStore; ++j) {
+        const int r = j * kRowsPerStore + st_row;
+        const bf16x8 w = *reinterpret_cast<LDS_PTR(const bf16x8)>(ep + r * kOutStride + st_chunk * 16);
+        if (kv0w + r < kv_end) *reinterpret_cast<bf16x8*>(out + ((size_t)(kv0w + r) * Hkv + hk) * D + st_chunk * 8) = w;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
     const int my_key = kv0w + 32 * kb + l32;
