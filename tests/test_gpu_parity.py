@@ -117,6 +117,28 @@ def test_bf16_small_packs_full_oracle(hq, hkv, d, slice_size):
     _run_modes(prob, ref, TOL_O, TOL_G, f"bf16 {hq}/{hkv}/{d}/S{slice_size}")
 
 
+@pytest.mark.parametrize("seed", [103, 104, 108, 115, 124, 126])
+def test_bf16_random_packs(seed):
+    """Seeded random packs: length mixes with empty, one-row, sub-tile and multi-tile samples, slice sizes that are
+    no multiple of any tile, group sizes 1..8 at both head dims, so that ragged query tiles, slices that start
+    inside a key tile, persistent blocks with more work numbers than blocks and with fewer all occur."""
+    r = np.random.default_rng(seed)
+    n = int(r.integers(3, 40))
+    L = [int(x) for x in np.minimum(r.pareto(1.2, n) * 60, 1500).astype(np.int64)]
+    L[int(r.integers(0, n))] = 1
+    hkv = int(r.choice([1, 2, 3]))
+    g = int(r.choice([1, 2, 4, 8]))
+    d = int(r.choice([64, 128]))
+    slice_size = int(r.integers(40, 700))
+    cu, sl, fu, bu = _tables(L, slice_size, ("TOKEN_CAP", {"cap": int(r.integers(200, 1500))}),
+                             ("PREFIX_FILL", {"m": int(r.integers(2, 7)), "w_quad": 5, "w_lin": 0, "backward": True}))
+    q, k, v, dO = _draw(sum(L), hkv * g, hkv, d, seed, True, 0.5, 0.1)
+    scale = d ** -0.5
+    ref = _oracle(q, k, v, dO, cu, scale)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    _run_modes(prob, ref, TOL_O, TOL_G, f"random pack seed {seed}: n {n} T {sum(L)} {hkv * g}/{hkv}/{d} S{slice_size}")
+
+
 def test_bf16_unit_variance_inputs():
     # N(0,1) inputs (larger scores, sharper softmax) still inside the stated tolerances
     L = [300, 77]
