@@ -275,6 +275,7 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
       for (int r = 0; r < 16; ++r) negm[hb][r] = -m_ref[hb];
       asm volatile("" : "+v"(negm[hb]));
     }
+    settle_writes(negm[0], negm[1]);                    // vector writes, then asm products reading them as C operands
   };
   // Start of a score phase: the lazy test for the unit just finished, the mask.
   auto boundary = [&](auto kbc, auto checkc, auto maskc) {
