@@ -226,10 +226,13 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = it.kv_start + t * kDqBK;
-    // next tile straight into the other buffer (zeros past the end of the tensor; unused then)
+    // next tile straight into the other buffer (not behind the last one: the wait that ends the iteration would
+    // sit out the latency of loads nobody needs)
     const int nb = ((t + 1) & 1) * kBufBytes;
-    stage_tile<D, kDqBK, 256>(lds + nb, srcK, (t + 1) * kDqBK, tid);
-    stage_tile<D, kDqBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kDqBK, tid);
+    if (t + 1 < n_tiles) {
+      stage_tile<D, kDqBK, 256>(lds + nb, srcK, (t + 1) * kDqBK, tid);
+      stage_tile<D, kDqBK, 256>(lds + nb + kTileBytes, srcV, (t + 1) * kDqBK, tid);
+    }
     const int rel = my_row - j0 - 4 * half;
     if (j0 + kDqBK - 1 <= q0w) {
       dq_tile<D, false>(pk, pkt, qf, dof, acc, negl, negd, rel);

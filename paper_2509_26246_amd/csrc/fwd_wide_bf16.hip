@@ -299,6 +299,12 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
     bf16x8 ka[2][NKS];
     Tr1 va[2][NVF];
     constexpr int kPasses = kTileBytes<D> / 4096, kRowsPerPass = 4096 / kRowBytes<D>;
+    // Tiles behind the item's last are not fetched: their loads get an offset beyond the tensor (the hardware's range
+    // check answers with zeros at once), so that the wait that ends the item's last iterations does not sit out
+    // the latency of loads nobody needs; the number of loads per iteration stays fixed.
+    constexpr int kBeyond = 0x7FF00000;
+    const int ksoff_k = t + 2 < n_tiles ? ksoff : kBeyond;
+    const int ksoff_v = t + 1 < n_tiles ? ksoff - kKeys * srcK.row_bytes : kBeyond;
 
     auto ew = [&](auto kec, auto jc) {                  // the element-wise slots behind product slot j of a half
       constexpr int KE = decltype(kec)::value, j = decltype(jc)::value;
@@ -361,7 +367,7 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
       if constexpr (!first && p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
         constexpr int pass = (p - 2 * NDB) / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(srcK.rsrc, lds + kdst + pass * 4096, 16, srcK.voff,
-                                                 ksoff + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
+                                                 ksoff_k + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
       }
     };
     auto extra_a1 = [&](auto pc) {                      // V(t+1) staged
@@ -369,7 +375,7 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
       if constexpr (!first && p > 2 * NDB && (p - 2 * NDB) % 2 == 1 && (p - 2 * NDB) / 2 < kPasses) {
         constexpr int pass = (p - 2 * NDB) / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(srcV.rsrc, lds + vdst + pass * 4096, 16, srcV.voff,
-                                                 ksoff - kKeys * srcK.row_bytes + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
+                                                 ksoff_v + pass * kRowsPerPass * srcK.row_bytes, 0, 0);
       }
     };
     auto extra_b1 = [&](auto pc) {                      // K pointers to the next iteration's buffer
