@@ -49,6 +49,21 @@ def test_golden_cfg0_tables_from_native_builder():
     assert sum(S.slice_pairs(r) for r in sl) == g["pairs_total"]
 
 
+def test_golden_hand_worked_policies_from_native_builder():
+    # the same hand-worked fixture the table oracle is pinned to, against the C++ builder: the two
+    # implementations are compared with what the rules give on paper, not only with each other
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "policies_tiny.json")))
+    for key in ("input_A", "input_B"):
+        inp = g[key]
+        cu, sl = S.build_slices(inp["lengths"], inp["slice_size"])
+        assert cu.tolist() == inp["cu"]
+        assert [S.slice_pairs(r) for r in sl] == inp["pairs"] and sl[:, 3].tolist() == inp["q_len"]
+        for case in inp["cases"]:
+            up, us = S.build_units(cu, sl, case["policy"], **case["params"])
+            units = [us[up[u]:up[u + 1]].tolist() for u in range(len(up) - 1)]
+            assert units == case["units"], (key, case["policy"], case["params"], units)
+
+
 @pytest.mark.parametrize("policy,params", POLICIES)
 def test_native_policies_bit_exact_vs_oracle(policy, params):
     r = np.random.default_rng(7)

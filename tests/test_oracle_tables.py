@@ -11,6 +11,27 @@ import workloads as W
 from oracle import tables as T
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "cfg0_tables.json")
+GOLD_POLICIES = os.path.join(os.path.dirname(__file__), "golden", "policies_tiny.json")
+
+
+def _units(up, us):
+    return [us[up[u]:up[u + 1]].tolist() for u in range(len(up) - 1)]
+
+
+def _golden_policy_mismatches(build_slices, build_units):
+    """Every case of the hand-worked fixture that (build_slices, build_units) does not reproduce."""
+    g = json.load(open(GOLD_POLICIES))
+    bad = []
+    for key in ("input_A", "input_B"):
+        inp = g[key]
+        cu, sl = build_slices(inp["lengths"], inp["slice_size"])
+        assert cu.tolist() == inp["cu"]
+        assert [T.pairs_of_slice(r) for r in sl] == inp["pairs"] and [int(r[3]) for r in sl] == inp["q_len"]
+        for case in inp["cases"]:
+            up, us = build_units(cu, sl, case["policy"], **case["params"])
+            if _units(up, us) != case["units"]:
+                bad.append((key, case["policy"], case["params"], _units(up, us)))
+    return bad
 
 
 def test_golden_cfg0_tables():
@@ -24,6 +45,61 @@ def test_golden_cfg0_tables():
     assert up.tolist() == g["bwd_unit_ptr"] and us.tolist() == g["bwd_unit_slices"]
     assert sum(T.pairs_of_slice(r) for r in sl) == g["pairs_total"]
     assert [T.pairs_of_sample(L) for L in g["lengths"]] == g["pairs_per_sample"]
+
+
+def test_golden_hand_worked_policies():
+    """PREFIX_FILL (forward, backward, mixed cost), TOKEN_CAP, SEEDED_LPT, ISOLATE_FILL, PER_SAMPLE and
+    ROUND_ROBIN on two tiny inputs worked by hand; the inputs are chosen so that a start-point or end-point
+    rule in place of the midpoint rule, or an ISOLATE_FILL that fills m instead of m - n_isolated units,
+    gives other lists (the fixture records those too)."""
+    assert _golden_policy_mismatches(T.build_slices, T.build_units) == []
+    g = json.load(open(GOLD_POLICIES))
+    for inp in (g["input_A"], g["input_B"]):
+        cu, sl = T.build_slices(inp["lengths"], inp["slice_size"])
+        assert T._walk(cu, sl, False) == inp["walk_forward"] and T._walk(cu, sl, True) == inp["walk_backward"]
+        for case in inp["cases"]:
+            for wrong in ("start_point_units", "end_point_units", "fill_m_units"):
+                assert case.get(wrong) != case["units"]
+            flat = sorted(t for u in case["units"] for t in u)
+            assert flat == list(range(len(sl)))
+
+
+def test_golden_catches_planted_rule_changes(monkeypatch):
+    """A mistake planted in the oracle (here, on the CPU) must fail the fixture: the start-point and the
+    end-point variants of the fill rule, and a walk that ignores the descending-length order."""
+    real_fill, real_walk = T._prefix_fill, T._walk
+
+    def fill_variant(kind):
+        def f(walk, slices, m, w_quad, w_lin):
+            total = sum(T._cost(slices[t], w_quad, w_lin) for t in walk)
+            groups = [[] for _ in range(m)]
+            before = 0
+            for t in walk:
+                c = T._cost(slices[t], w_quad, w_lin)
+                num = before if kind == "start" else before + c
+                groups[min(m - 1, (m * num) // total if total > 0 else 0)].append(t)
+                before += c
+            return groups
+        return f
+
+    for kind in ("start", "end"):
+        monkeypatch.setattr(T, "_prefix_fill", fill_variant(kind))
+        bad = _golden_policy_mismatches(T.build_slices, T.build_units)
+        assert any(b[1] == "PREFIX_FILL" for b in bad), kind
+    monkeypatch.setattr(T, "_prefix_fill", lambda walk, slices, m, wq, wl: real_fill(walk, slices, m + 1, wq, wl))
+    assert any(b[1] == "ISOLATE_FILL" for b in _golden_policy_mismatches(T.build_slices, T.build_units))
+    monkeypatch.setattr(T, "_prefix_fill", real_fill)
+
+    def table_order_walk(cu, slices, backward):                      # samples in index order
+        out = []
+        for s in range(len(cu) - 1):
+            ts = [t for t in range(len(slices)) if int(slices[t][0]) == s]
+            out.extend(ts[::-1] if backward else ts)
+        return out
+    monkeypatch.setattr(T, "_walk", table_order_walk)
+    assert _golden_policy_mismatches(T.build_slices, T.build_units) != []
+    monkeypatch.setattr(T, "_walk", real_walk)
+    assert _golden_policy_mismatches(T.build_slices, T.build_units) == []
 
 
 def test_pairs_by_brute_force():
