@@ -1,15 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark: one step = slimattn_fwd + slimattn_bwd over every unit of one synthetic pack.
 
-Prints ONE JSON line (see --help).  The workload is the Llama-3-8B-shaped 32K-token pack
-(lognormal lengths, slices of 4096, 32 query / 8 KV heads, head_dim 128, bf16); the timed steps
-cycle over the packs drawn from the four fixed seeds, all resident in HBM before timing starts.
+Prints ONE JSON line.  The default workload is the Llama-3-8B-shaped 32K-token pack (lognormal lengths,
+slices of 4096, 32 query / 8 KV heads, head_dim 128, bf16); the timed steps cycle over the packs drawn from
+the four fixed seeds, all resident in HBM before timing starts.
+
+`value` is the fused launch (one launch per kernel over the whole unit list: the result does not depend on
+the grouping, so the unit lists then only decide validation).  The same line also carries `per_unit`: the
+same packs run one launch per unit in list order, which is how a pipeline runtime that receives one
+MicroPack at a time calls the library and the mode in which the forward and backward unit lists matter,
+with the spread of per-unit times.  `--per-unit` makes that mode the main measurement (and `value`).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -20,6 +27,12 @@ sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
+# The five counted tile products of the backward pass (scores, dP, dV, dK, dQ; 2*d*Hq flops per pair each)
+# are split between its two kernels so that they add up to the counted total: dK/dV kernel 3 (dK, dV and
+# half of the two recomputed products), dQ kernel 2; the forward kernel has 2.  What the kernels execute:
+# forward 2, dQ 3, dK/dV 4 products per tile, on whole tiles.
+CREDITED = {"fwd": 2, "dq": 2, "dkdv": 3}
+EXECUTED = {"fwd": 2, "dq": 3, "dkdv": 4}
 
 
 def _pack(w, seed):
@@ -30,7 +43,7 @@ def _pack(w, seed):
     return L, q, k, v, dO
 
 
-def _cpu_baseline(w, packs, budget_s=12.0):
+def _cpu_baseline(w, packs, seed, budget_s=12.0):
     """The fp64 oracle (forward + backward, unsliced definition) timed on host cores over a bounded
     sample: (sample, query head) items of the first pack, longest samples first, until the budget
     is used.  Throughput counts causal-effective flops, like the GPU figure."""
@@ -45,6 +58,8 @@ def _cpu_baseline(w, packs, budget_s=12.0):
     for h in range(w.n_q_heads):
         for s in order:
             a, b = int(cu[s]), int(cu[s + 1])
+            if b - a > 16384:                     # one such item alone would outlast the budget many times
+                continue
             qq, kk, vv, dd = q[a:b, h:h + 1], k[a:b, h // g:h // g + 1], v[a:b, h // g:h // g + 1], dO[a:b, h:h + 1]
             o, lse = A.fwd_sample(qq, kk, vv, scale)
             A.bwd_sample(qq, kk, vv, o, lse, dd, scale)
@@ -59,8 +74,60 @@ def _cpu_baseline(w, packs, budget_s=12.0):
     dt = time.perf_counter() - t0
     cores = len(os.sched_getaffinity(0))
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{items} (sample, query-head) items of the seed-{1} pack, longest samples first, fwd+bwd fp64, "
-                      f"{dt:.1f} s"}
+            "sample": f"{items} (sample, query-head) items of the seed-{seed} pack (samples up to 16384 rows), longest "
+                      f"first, fwd+bwd fp64, {dt:.1f} s"}
+
+
+def _runs_of_scope(sl, ids):
+    """Slices of one launch scope -> runs of query rows (adjacent slices of a sample merged): (q_lo, q_hi, kv_start)."""
+    rec = sorted((int(sl[t][2]), int(sl[t][2] + sl[t][3]), int(sl[t][4]), int(sl[t][0])) for t in ids)
+    runs = []
+    for a, b, ks, smp in rec:
+        if runs and runs[-1][3] == smp and runs[-1][1] == a:
+            runs[-1][1] = b
+        else:
+            runs.append([a, b, ks, smp])
+    return runs
+
+
+def _executed_pairs(runs, q_tile=128, k_tile_fwd=64, kv_tile=256, q_step=32):
+    """(query, key) pairs per query head the kernels run products on, whole tiles included: the forward's blocks
+    (128 rows, every wave walks all 64-key tiles of the block), the dQ kernel's waves (32 rows, tiles up to the
+    wave's diagonal), the dK/dV kernel's blocks (256 keys against steps of 32 query rows at or after them)."""
+    fwd = dq = dkdv = 0
+    by_sample = {}
+    for a, b, ks, smp in runs:
+        by_sample.setdefault(smp, []).append((a, b, ks))
+        for r0 in range(a, b, q_tile):
+            q_end = min(b, r0 + q_tile)
+            n_tiles = (q_end - ks + k_tile_fwd - 1) // k_tile_fwd
+            fwd += n_tiles * q_tile * k_tile_fwd
+            for wv in range(4):
+                q0w = r0 + 32 * wv
+                dq += min(n_tiles, (q0w + 31 - ks) // k_tile_fwd + 1) * 32 * k_tile_fwd
+    for rs in by_sample.values():
+        ks, kv_end = rs[0][2], rs[-1][1]
+        for k0 in range(ks, kv_end, kv_tile):
+            steps = sum((b - max(a, k0) + q_step - 1) // q_step for a, b, _ in rs if b > k0)
+            dkdv += steps * q_step * kv_tile
+    return {"fwd": fwd, "dq": dq, "dkdv": dkdv}
+
+
+def _algorithmic_bytes(T, hq, hkv, d, e=2):
+    """HBM bytes one fused launch of each kernel has to move at least (every tensor once)."""
+    return {"fwd": e * (2 * T * hq * d + 2 * T * hkv * d) + 4 * T * hq,
+            "dq": e * (4 * T * hq * d + 2 * T * hkv * d) + 20 * T * hq,
+            "dkdv": e * (2 * T * hq * d + 4 * T * hkv * d) + 16 * T * hq}
+
+
+def _spread(xs):
+    xs = [float(x) for x in xs]
+    if not xs:
+        return None
+    mean = sum(xs) / len(xs)
+    sd = (sum((x - mean) ** 2 for x in xs) / len(xs)) ** 0.5
+    return {"n_units": len(xs), "min_ms": min(xs), "median_ms": statistics.median(xs), "max_ms": max(xs),
+            "cv": sd / mean if mean > 0 else 0.0}
 
 
 def main():
@@ -70,7 +137,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg1_llama8b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--per-unit", action="store_true", help="one launch per unit instead of one fused launch")
+    ap.add_argument("--per-unit", action="store_true", help="main measurement: one launch per unit instead of one fused launch")
+    ap.add_argument("--seeds", default="", help="comma-separated subset of the workload's seeds (default: all four)")
+    ap.add_argument("--brief", action="store_true", help="skip the per-seed and the secondary per-unit measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -86,21 +155,26 @@ def main():
         sys.exit(1)
     S.load_library()                      # fails loudly if the HIP library is missing
     w = W.WORKLOADS[args.workload]
-    packs = [_pack(w, seed) for seed in W.SEEDS]
-    probs, pairs = [], []
+    seeds = [int(x) for x in args.seeds.split(",")] if args.seeds else list(W.SEEDS)
+    packs = [_pack(w, seed) for seed in seeds]
+    d, hq, hkv = w.head_dim, w.n_q_heads, w.n_kv_heads
+    probs, pairs, tabs, build_ms = [], [], [], {"slices_and_units": [], "derive_and_upload": []}
     for L, q, k, v, dO in packs:
+        t0 = time.perf_counter()
         cu, sl = S.build_slices(L, w.slice_size)
         fu = S.build_units(cu, sl, w.fwd_policy[0], **w.fwd_policy[1])
         bu = S.build_units(cu, sl, w.bwd_policy[0], **w.bwd_policy[1])
+        t1 = time.perf_counter()
+        torch.cuda.set_device(0)
+        tmp = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1])      # timed on its own: derived work-lists + one upload
+        t2 = time.perf_counter()
+        tmp.destroy()
+        build_ms["slices_and_units"].append((t1 - t0) * 1e3)
+        build_ms["derive_and_upload"].append((t2 - t1) * 1e3)
         probs.append(H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=(w.dtype == "bf16")))
         pairs.append(int(sum(S.slice_pairs(r) for r in sl)))
-    flags = S.FLAG_PER_UNIT_LAUNCH if args.per_unit else 0
-    d, hq = w.head_dim, w.n_q_heads
-
-    def step(i):
-        p = probs[i % len(probs)]
-        p.forward(flags=flags)
-        p.backward(flags=flags)
+        tabs.append((cu, sl, fu, bu))
+    n_packs = len(probs)
 
     # A plain device copy of known size (256 MiB read + 256 MiB written) before anything else: under
     # `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` it calibrates the counters' units for roofline.traffic.
@@ -108,64 +182,162 @@ def main():
     cal2 = torch.empty_like(cal)
     cal2.copy_(cal)
     del cal, cal2
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    S.profile_enable(64 * max(args.steps, 1) if args.per_unit else 8 * max(args.steps, 1))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
+
+    def launches_per_step(p):
+        return p.tables.n_fwd_units + 5 * p.tables.n_bwd_units + 8
+
+    def measure(flags, steps, warmup, which=None):
+        """Runs warmup + steps over the packs `which` (default: all, cycling); returns wall seconds, pairs done and
+        the per-launch records (class, pass, unit, ms)."""
+        idx = list(range(n_packs)) if which is None else list(which)
+        for i in range(warmup):
+            p = probs[idx[i % len(idx)]]
+            p.forward(flags=flags); p.backward(flags=flags)
+        torch.cuda.synchronize()
+        S.profile_enable(sum(launches_per_step(probs[idx[i % len(idx)]]) for i in range(steps)) + 16)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            p = probs[idx[i % len(idx)]]
+            p.forward(flags=flags); p.backward(flags=flags)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        rec = S.profile_read_launches()
+        S.profile_enable(0)
+        return t1 - t0, sum(pairs[idx[i % len(idx)]] for i in range(steps)), rec
+
+    def summarise(wall, tot_pairs, rec, steps):
+        cls, ps, un, ms = rec
+        per = {c: (float(ms[cls == i].sum()), int((cls == i).sum())) for i, c in enumerate(S.KERNEL_CLASSES)}
+        fwd_flops, bwd_flops = S.flops_fwd(tot_pairs, d, hq), S.flops_bwd(tot_pairs, d, hq)
+        fwd_ms = per["fwd"][0]
+        bwd_ms = sum(per[c][0] for c in ("delta", "dq", "dkdv", "finalize", "fill"))
+        out = {"value": (fwd_flops + bwd_flops) / wall / 1e12, "ms_per_step": wall * 1e3 / max(steps, 1),
+               "fwd_tflops": fwd_flops / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0,
+               "bwd_tflops": bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0,
+               "kernel_ms_per_step": {c: per[c][0] / max(steps, 1) for c in per}}
+        out["fwd_pct_bf16_peak"] = 100 * out["fwd_tflops"] / BF16_MFMA_PEAK_TFLOPS
+        out["bwd_pct_bf16_peak"] = 100 * out["bwd_tflops"] / BF16_MFMA_PEAK_TFLOPS
+        return out, per
+
+    def unit_spread(rec, steps):
+        """Time of each scheduling unit (all kernels launched for it), averaged over the steps in which the same
+        pack ran; spread over the units of all packs.  Only launches tied to a unit count."""
+        cls, ps, un, ms = rec
+        step, prev_pass, acc = 0, 0, {}
+        for p_, u, m in zip(ps, un, ms):                # launches come in step order: forward, then backward
+            if p_ == 0 and prev_pass == 1:
+                step += 1
+            prev_pass = p_
+            if u >= 0:
+                key = (int(p_), step % n_packs, int(u))
+                tot, cnt = acc.get(key, (0.0, set()))
+                cnt.add(step)
+                acc[key] = (tot + float(m), cnt)
+        out = {}
+        for name, pss in (("fwd", 0), ("bwd", 1)):
+            xs = [tot / len(cnt) for (p_, _, _), (tot, cnt) in acc.items() if p_ == pss]
+            if xs:
+                out[name] = _spread(xs)
+        return out
+
+    main_flags = S.FLAG_PER_UNIT_LAUNCH if args.per_unit else 0
+    wall, tot_pairs, rec = measure(main_flags, args.steps, args.warmup)
+    main_sum, per = summarise(wall, tot_pairs, rec, args.steps)
+
+    # Per kernel: algorithmic and executed throughput, algorithmic HBM rate.  Executed pairs and bytes are those
+    # of the scopes the main measurement launched.
+    T_mean = sum(int(p.tables.total_tokens) for p in probs) / n_packs
+    alg_bytes = _algorithmic_bytes(T_mean, hq, hkv, d)
+    exec_pairs = {"fwd": 0, "dq": 0, "dkdv": 0}
     for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = S.profile_read()
-    S.profile_enable(0)
+        cu, sl, fu, bu = tabs[i % n_packs]
+        if args.per_unit:
+            for c, (up, us) in (("fwd", fu), ("bwd", bu)):
+                for u in range(len(up) - 1):
+                    e = _executed_pairs(_runs_of_scope(sl, us[up[u]:up[u + 1]]))
+                    if c == "fwd":
+                        exec_pairs["fwd"] += e["fwd"]
+                    else:
+                        exec_pairs["dq"] += e["dq"]; exec_pairs["dkdv"] += e["dkdv"]
+        else:
+            e = _executed_pairs(_runs_of_scope(sl, range(len(sl))))
+            for c in exec_pairs:
+                exec_pairs[c] += e[c]
+    kernels = {}
+    for c in ("fwd", "dq", "dkdv"):
+        ms_c, n_c = per[c]
+        if ms_c <= 0:
+            continue
+        sec = ms_c * 1e-3
+        kernels[c] = {"avg_launch_ms": ms_c / max(n_c, 1), "launches": n_c,
+                      "algorithmic_tflops": CREDITED[c] * 2 * d * hq * tot_pairs / sec / 1e12,
+                      "executed_mfma_tflops": EXECUTED[c] * 2 * d * hq * exec_pairs[c] / sec / 1e12,
+                      "tile_padding": exec_pairs[c] / max(tot_pairs, 1)}
+        kernels[c]["frac_of_bf16_peak"] = kernels[c]["algorithmic_tflops"] / BF16_MFMA_PEAK_TFLOPS
+        if not args.per_unit:
+            kernels[c]["hbm_gbs_algorithmic"] = alg_bytes[c] * args.steps / sec / 1e9
+            kernels[c]["hbm_frac_of_peak_algorithmic"] = kernels[c]["hbm_gbs_algorithmic"] / HBM_PEAK_GBS
 
-    step_pairs = [pairs[i % len(probs)] for i in range(args.steps)]
-    tot_pairs = sum(step_pairs)
-    fwd_flops = S.flops_fwd(tot_pairs, d, hq)
-    bwd_flops = S.flops_bwd(tot_pairs, d, hq)
-    wall = t1 - t0
-    fwd_ms = prof["fwd"][0]
-    bwd_ms = sum(prof[c][0] for c in ("delta", "dq", "dkdv", "finalize", "fill"))
-    value = (fwd_flops + bwd_flops) / wall / 1e12
-    fwd_tf = fwd_flops / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0
-    bwd_tf = bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
-
-    # Roofline of the dominant kernel (largest share of kernel time).  The five counted tile products
-    # of the backward pass (scores, dP, dV, dK, dQ; 2*d*Hq flops per pair each) are split between its
-    # two kernels so that they add up to the counted total: dK/dV kernel 3 (dK, dV and half of the two
-    # recomputed products), dQ kernel 2; the forward kernel has 2.
-    share = {"fwd": 2, "dq": 2, "dkdv": 3}
-    dom = max(share, key=lambda c: prof[c][0])
-    dom_ms, dom_n = prof[dom]
-    dom_flops = share[dom] * 2 * d * hq * tot_pairs
+    # Roofline of the dominant kernel (largest share of kernel time).  `traffic` (HBM bytes per launch from
+    # rocprofv3 counters) is not measured by this run: it is read from the committed summary of a profiling
+    # run of this command, and only when that summary names this workload and launch mode.
+    dom = max(CREDITED, key=lambda c: per[c][0])
+    dom_ms, dom_n = per[dom]
+    dom_flops = CREDITED[dom] * 2 * d * hq * tot_pairs
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{dom}_{args.workload}.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    mode = "per-unit" if args.per_unit else "fused"
+    traffic, traffic_src = None, None
+    for c in ("fwd", "dq", "dkdv"):
+        tpath = os.path.join(ROOT, "profiles", f"traffic_{c}_{args.workload}_{mode}.json")
+        if os.path.exists(tpath) and c in kernels:
+            tj = json.load(open(tpath))
+            kernels[c]["hbm_bytes_per_launch_measured"] = tj.get("hbm_bytes_per_launch")
+            kernels[c]["hbm_gbs_measured"] = tj["hbm_bytes_per_launch"] / (kernels[c]["avg_launch_ms"] * 1e-3) / 1e9
+            kernels[c]["hbm_traffic_source"] = tj.get("source")
+            if c == dom:
+                traffic, traffic_src = tj.get("hbm_bytes_per_launch"), tj.get("source")
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
+                "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                 "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": dom_n,
                 "algorithmic_flops_per_launch": dom_flops / max(dom_n, 1)}
 
     out = {
         "metric": "causal-effective attention TFLOP/s fwd & bwd (sliced varlen) + % bf16 MFMA peak",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall * 1e3 / max(args.steps, 1), "higher_is_better": True, "scaling": "weak",
+        "value": main_sum["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_sum["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "total_tokens": w.total_tokens, "n_q_heads": hq,
-                   "n_kv_heads": w.n_kv_heads, "head_dim": d, "slice_size": w.slice_size, "seeds": list(W.SEEDS),
-                   "launch": "per-unit" if args.per_unit else "fused", "fwd_policy": w.fwd_policy[0],
-                   "bwd_policy": w.bwd_policy[0]},
-        "fwd_tflops": fwd_tf, "bwd_tflops": bwd_tf,
-        "fwd_pct_bf16_peak": 100 * fwd_tf / BF16_MFMA_PEAK_TFLOPS, "bwd_pct_bf16_peak": 100 * bwd_tf / BF16_MFMA_PEAK_TFLOPS,
-        "kernel_ms_per_step": {c: prof[c][0] / max(args.steps, 1) for c in prof},
+        "config": {"workload": args.workload, "total_tokens": w.total_tokens if w.total_tokens > 0 else int(T_mean),
+                   "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d, "slice_size": w.slice_size, "seeds": seeds,
+                   "launch": mode, "fwd_policy": w.fwd_policy[0], "bwd_policy": w.bwd_policy[0],
+                   "fwd_units": [p.tables.n_fwd_units for p in probs], "bwd_units": [p.tables.n_bwd_units for p in probs]},
+        "fwd_tflops": main_sum["fwd_tflops"], "bwd_tflops": main_sum["bwd_tflops"],
+        "fwd_pct_bf16_peak": main_sum["fwd_pct_bf16_peak"], "bwd_pct_bf16_peak": main_sum["bwd_pct_bf16_peak"],
+        "kernel_ms_per_step": main_sum["kernel_ms_per_step"], "kernels": kernels,
+        "table_build_ms": {k_: statistics.median(v_) for k_, v_ in build_ms.items()},
         "roofline": roofline,
     }
+    if args.per_unit:
+        out["unit_ms"] = unit_spread(rec, args.steps)
+
+    if not args.brief:
+        # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
+        per_seed = {}
+        for i, seed in enumerate(seeds):
+            wl, pr, rc = measure(main_flags, 6, 2, which=[i])
+            s_, _ = summarise(wl, pr, rc, 6)
+            per_seed[str(seed)] = {"value": s_["value"], "fwd_tflops": s_["fwd_tflops"], "bwd_tflops": s_["bwd_tflops"],
+                                   "pairs": pairs[i], "samples": int(len(packs[i][0])), "longest": int(packs[i][0].max())}
+        out["per_seed"] = per_seed
+        out["value_median_over_seeds"] = statistics.median(v_["value"] for v_ in per_seed.values())
+        if not args.per_unit:
+            # the same packs, one launch per unit in list order
+            wl, pr, rc = measure(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
+            s_, _ = summarise(wl, pr, rc, args.steps)
+            s_["unit_ms"] = unit_spread(rc, args.steps)
+            out["per_unit"] = s_
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = _cpu_baseline(w, packs)
+        out["cpu_baseline"] = _cpu_baseline(w, packs, seeds[0])
     print(json.dumps(out))
 
 

@@ -196,15 +196,25 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
 #define SLIMATTN_K_COUNT     6
 
 /* Per-kernel timing for benchmarks (the paper calibrates its simulator from such primitive
- * measurements, Primitive Measurements and Search Space).  max_launches > 0: create that many
+ * measurements, Primitive Measurements and Search Space; its Workload Balance Studies compare the
+ * forward and backward time of each scheduling unit).  max_launches > 0: create that many
  * HIP event pairs on the current device; from then on every kernel launch made by slimattn_fwd /
- * slimattn_bwd is bracketed by two events recorded on the launch's own stream until the pool is
- * used up.  max_launches == 0: stop and destroy the events.  Not thread-safe; one device. */
+ * slimattn_bwd is bracketed by two events recorded on the launch's own stream.  A launch that finds
+ * the pool used up runs untimed and is counted as dropped.  max_launches == 0: stop and destroy the
+ * events.  Not thread-safe; one device. */
 int slimattn_profile_enable(int32_t max_launches);
 
 /* Waits for the recorded events, adds up elapsed milliseconds and launch counts per kernel class
- * into ms[SLIMATTN_K_COUNT] and launches[SLIMATTN_K_COUNT] (HOST), and rewinds the pool. */
+ * into ms[SLIMATTN_K_COUNT] and launches[SLIMATTN_K_COUNT] (HOST), and rewinds the pool.  Returns
+ * SLIMATTN_ECAP (the sums are still written) when launches were dropped since the last read. */
 int slimattn_profile_read(double* ms, int64_t* launches);
+
+/* The same per launch, in launch order: kernel class, pass (0 forward, 1 backward), unit index in that
+ * pass's list (-1: the launch covered a whole range or is not tied to a unit) and milliseconds.  All
+ * arrays HOST [cap]; *n_launches receives the number recorded, *dropped (optional) the number that found
+ * the pool used up.  ECAP when cap is too small (nothing is consumed); rewinds the pool on success. */
+int slimattn_profile_read_launches(int32_t cap, int32_t* cls, int32_t* pass, int32_t* unit, float* ms,
+                                   int32_t* n_launches, int64_t* dropped);
 
 const char* slimattn_strerror(int code);
 int slimattn_last_hip_error(void);       /* hipError_t of the last EHIP on this thread */

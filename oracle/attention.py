@@ -217,22 +217,24 @@ def dq_rows(q, k, v, do, cu, scale, rows, heads):
 def dkdv_rows(q, k, v, do, cu, scale, sample, kv_head, key_rows, block=2048):
     """Exact dK[j, kv_head, :], dV[j, kv_head, :] for global key rows `key_rows` of `sample`.
 
-    The row statistics (lse, delta) of every query of the sample and every head of the group are
-    computed first from the definition, then each requested key row sums over queries i >= j."""
+    A key row j sums over the queries i >= j of its sample only, so the row statistics (lse, delta) are
+    computed, from the definition, for the queries from the smallest requested key row on (each over its
+    whole prefix of keys) and for every head of the group; then each requested key row takes its sum."""
     g = q.shape[1] // k.shape[1]
     a, b = int(cu[sample]), int(cu[sample + 1])
     L = b - a
     kk = np.asarray(k[a:b, kv_head, :], F64)
     vv = np.asarray(v[a:b, kv_head, :], F64)
     key_local = np.asarray(key_rows) - a
+    first = int(key_local.min()) if len(key_local) else L      # queries before it are in no requested sum
     d_k = np.zeros((len(key_rows), kk.shape[1]), F64)
     d_v = np.zeros_like(d_k)
     for h in range(kv_head * g, (kv_head + 1) * g):
         qq = np.asarray(q[a:b, h, :], F64)
         dd = np.asarray(do[a:b, h, :], F64)
-        lse = np.empty(L, F64)
-        delta = np.empty(L, F64)
-        for r0 in range(0, L, block):
+        lse = np.full(L, np.nan, F64)
+        delta = np.full(L, np.nan, F64)
+        for r0 in range(first, L, block):
             r1 = min(L, r0 + block)
             s = scale * (qq[r0:r1] @ kk[:r1].T)
             s = np.where(np.arange(r1)[None, :] <= np.arange(r0, r1)[:, None], s, -np.inf)

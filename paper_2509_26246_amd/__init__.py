@@ -9,10 +9,10 @@ from .binding import (SlimAttnError, Tables, build_slices, build_slices_from_bou
                       slice_pairs, flops_fwd, flops_bwd, tables_create, bwd_workspace_bytes, fwd, bwd, strerror,
                       version, load_library, POLICY_KINDS, F32, BF16, FLAG_PER_UNIT_LAUNCH, FLAG_STATS_PREPASS, CHECK_FORWARD,
                       CHECK_BACKWARD, CHECK_ORDER, EXPORTED_SYMBOLS, profile_enable, profile_read,
-                      KERNEL_CLASSES)
+                      profile_read_launches, KERNEL_CLASSES)
 
 __all__ = ["SlimAttnError", "Tables", "build_slices", "build_slices_from_bounds", "build_units", "validate",
            "slice_pairs", "flops_fwd", "flops_bwd", "tables_create", "bwd_workspace_bytes", "fwd", "bwd",
            "strerror", "version", "load_library", "POLICY_KINDS", "F32", "BF16", "FLAG_PER_UNIT_LAUNCH", "FLAG_STATS_PREPASS",
            "CHECK_FORWARD", "CHECK_BACKWARD", "CHECK_ORDER", "EXPORTED_SYMBOLS", "profile_enable", "profile_read",
-           "KERNEL_CLASSES"]
+           "profile_read_launches", "KERNEL_CLASSES"]

@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = [
     "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
-    "slimattn_profile_read"]
+    "slimattn_profile_read", "slimattn_profile_read_launches"]
 KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "finalize", "fill"]
 
 
@@ -80,6 +80,8 @@ def load_library():
     lib.slimattn_version.restype = C.c_int
     lib.slimattn_profile_enable.argtypes = [C.c_int32]
     lib.slimattn_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.slimattn_profile_read_launches.argtypes = [C.c_int32, i32p, i32p, i32p, C.POINTER(C.c_float), i32p,
+                                                   C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -255,10 +257,31 @@ def profile_enable(max_launches: int) -> None:
 
 
 def profile_read():
-    """{kernel class: (total ms, launches)} since the last read."""
+    """{kernel class: (total ms, launches)} since the last read.  Raises if launches went untimed because the
+    event pool was too small (the sums would under-count)."""
     ms = (C.c_double * len(KERNEL_CLASSES))()
     n = (C.c_int64 * len(KERNEL_CLASSES))()
     rc = load_library().slimattn_profile_read(ms, n)
     if rc != 0:
-        raise SlimAttnError(rc, "slimattn_profile_read")
+        raise SlimAttnError(rc, "slimattn_profile_read", " (event pool too small: launches ran untimed)" if rc == -3 else "")
     return {name: (ms[i], n[i]) for i, name in enumerate(KERNEL_CLASSES)}
+
+
+def profile_read_launches():
+    """Per launch, in launch order: arrays (kernel class, pass, unit, ms).  Raises if launches were dropped."""
+    lib = load_library()
+    n, dropped = C.c_int32(0), C.c_int64(0)
+    rc = lib.slimattn_profile_read_launches(0, None, None, None, None, C.byref(n), C.byref(dropped))
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_profile_read_launches")
+    cap = n.value
+    cls, ps, un = (np.zeros(cap, np.int32) for _ in range(3))
+    ms = np.zeros(cap, np.float32)
+    if cap:
+        rc = lib.slimattn_profile_read_launches(cap, _p(cls), _p(ps), _p(un), ms.ctypes.data_as(C.POINTER(C.c_float)),
+                                                C.byref(n), C.byref(dropped))
+        if rc != 0:
+            raise SlimAttnError(rc, "slimattn_profile_read_launches")
+    if dropped.value:
+        raise SlimAttnError(-3, "slimattn_profile_read_launches", f" ({dropped.value} launches ran untimed)")
+    return cls, ps, un, ms

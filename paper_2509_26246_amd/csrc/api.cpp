@@ -40,19 +40,24 @@ int hip_rc(int e) {
 size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
 
 // Optional per-launch timing (slimattn_profile_enable).  Events are created up front; recording
-// an event allocates nothing.
+// an event allocates nothing.  A launch that finds the pool used up runs untimed and is counted as dropped.
 struct Profiler {
   std::vector<hipEvent_t> start, stop;
-  std::vector<int> cls;
+  std::vector<int> cls, pass, unit;
   size_t used = 0;
+  int64_t dropped = 0;
   bool on = false;
+  int cur_pass = 0, cur_unit = -1;      // what the launches being issued belong to (set by the entry points)
 } g_prof;
 
 template <class F>
 int timed(int cls, void* stream, F&& launch) {
-  if (!g_prof.on || g_prof.used >= g_prof.start.size()) return launch();
+  if (!g_prof.on) return launch();
+  if (g_prof.used >= g_prof.start.size()) { ++g_prof.dropped; return launch(); }
   const size_t i = g_prof.used++;
   g_prof.cls[i] = cls;
+  g_prof.pass[i] = g_prof.cur_pass;
+  g_prof.unit[i] = g_prof.cur_unit;
   (void)hipEventRecord(g_prof.start[i], (hipStream_t)stream);
   const int e = launch();
   (void)hipEventRecord(g_prof.stop[i], (hipStream_t)stream);
@@ -83,12 +88,15 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
     });
   };
   const bool whole = lo == 0 && hi == t->n_units[0];
+  g_prof.cur_pass = 0;
+  g_prof.cur_unit = -1;
   if (whole && !(p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH))
     return hip_rc(run(t->d_fused.q_items[z], (int)t->fused.q_items[z].size()));
   const auto& off = t->per_unit[0].q_off[z];
   if (!(p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH))
     return hip_rc(run(t->d_per_unit[0].q_items[z] + off[lo], off[hi] - off[lo]));
   for (int u = lo; u < hi; ++u) {
+    g_prof.cur_unit = u;
     rc = hip_rc(run(t->d_per_unit[0].q_items[z] + off[u], off[u + 1] - off[u]));
     if (rc != SLIMATTN_OK) return rc;
   }
@@ -117,25 +125,29 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   const LaunchCtx ctx{p, stream, t->total_tokens};
   const int n_units = t->n_units[1];
   const bool whole = lo == 0 && hi == n_units;
+  g_prof.cur_pass = 1;
+  g_prof.cur_unit = -1;
   const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
 
-  // Row statistic delta_i = dO_i . o_i.  fp32: one prepass for every row and head at the first call, later
-  // calls reuse it.  bf16: normally the dQ kernel computes it for the rows it owns and stores it (with lse in
-  // log2 units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
+  // Row statistic delta_i = dO_i . o_i, always for the query rows of the launch scope only (a caller that runs the
+  // list one unit at a time need not have o, lse and dO of later units yet).  fp32: a prepass in front of each
+  // dQ launch.  bf16: normally the dQ kernel computes it for the rows it owns and stores it (with lse in log2
+  // units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
   // With a very long sample (its K and V, over all KV heads, far beyond what the caches hold) the dQ blocks
   // depend on streaming the same K/V tiles at the same time, and the longer prologue cost 9 % there
-  // (256K sample); then a prepass stores the statistics for every row, as in fp32 mode.
+  // (256K sample); then a prepass stores the statistics, as in fp32 mode.
   const bool own_stats = !f32 && !(p->flags & SLIMATTN_FLAG_STATS_PREPASS) &&
                          (size_t)t->max_sample_len * p->n_kv_heads * p->head_dim * 4 <= (size_t(128) << 20);
-  if (lo == 0 && !own_stats) {
-    rc = hip_rc(timed(SLIMATTN_K_DELTA, stream, [&] {
-      return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta) : launch_bwd_stat_bf16(ctx, o, dO, lse, stat3);
-    }));
-    if (rc != SLIMATTN_OK) return rc;
-  }
   const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
   const int zk = tile_index(dkdv_kv_tile(p->dtype, p->head_dim));
   auto run_dq = [&](const QItem* items, int n) -> int {
+    if (!own_stats) {
+      const int e = timed(SLIMATTN_K_DELTA, stream, [&] {
+        return f32 ? launch_bwd_delta_f32(ctx, (const float*)o, (const float*)dO, delta, items, n)
+                   : launch_bwd_stat_bf16(ctx, o, dO, lse, stat3, items, n);
+      });
+      if (e != 0) return e;
+    }
     return timed(SLIMATTN_K_DQ, stream, [&] {
       return f32 ? launch_bwd_dq_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse, delta,
                                      (float*)dQ, items, n)
@@ -189,6 +201,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     // Units run one after another on the stream; each adds its queries' contributions to the
     // accumulators of every key tile of the prefix it sees (read-modify-write by the tile's
     // single owner), so the summation order is the unit order.
+    g_prof.cur_unit = u;
     if (per_unit) {
       rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));
       if (rc != SLIMATTN_OK) return rc;
@@ -197,6 +210,7 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
                     : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u, 1, 0));
     if (rc != SLIMATTN_OK) return rc;
   }
+  g_prof.cur_unit = -1;
   if (hi == n_units) {
     rc = hip_rc(timed(SLIMATTN_K_FINALIZE, stream, [&] {
       return f32 ? launch_finalize_f32(ctx, acc_dk, acc_dv, (float*)dK, (float*)dV)
@@ -212,18 +226,44 @@ int slimattn_profile_enable(int32_t max_launches) {
   g_prof.start.clear();
   g_prof.stop.clear();
   g_prof.cls.clear();
+  g_prof.pass.clear();
+  g_prof.unit.clear();
   g_prof.used = 0;
+  g_prof.dropped = 0;
   g_prof.on = false;
   if (max_launches <= 0) return SLIMATTN_OK;
   g_prof.start.resize(max_launches);
   g_prof.stop.resize(max_launches);
   g_prof.cls.assign(max_launches, 0);
+  g_prof.pass.assign(max_launches, 0);
+  g_prof.unit.assign(max_launches, -1);
   for (int32_t i = 0; i < max_launches; ++i) {
     hipError_t e = hipEventCreate(&g_prof.start[i]);
     if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
     if (e != hipSuccess) return hip_rc((int)e);
   }
   g_prof.on = true;
+  return SLIMATTN_OK;
+}
+
+int slimattn_profile_read_launches(int32_t cap, int32_t* cls, int32_t* pass, int32_t* unit, float* ms, int32_t* n_launches,
+                                   int64_t* dropped) {
+  if (!n_launches || cap < 0 || (cap > 0 && (!cls || !pass || !unit || !ms))) return SLIMATTN_EINVAL;
+  *n_launches = (int32_t)g_prof.used;
+  if (dropped) *dropped = g_prof.dropped;
+  if ((size_t)cap < g_prof.used) return SLIMATTN_ECAP;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, g_prof.start[i], g_prof.stop[i]);
+    if (e != hipSuccess) return hip_rc((int)e);
+    cls[i] = g_prof.cls[i];
+    pass[i] = g_prof.pass[i];
+    unit[i] = g_prof.unit[i];
+    ms[i] = t;
+  }
+  g_prof.used = 0;
+  g_prof.dropped = 0;
   return SLIMATTN_OK;
 }
 
@@ -238,8 +278,10 @@ int slimattn_profile_read(double* ms, int64_t* launches) {
     ms[g_prof.cls[i]] += t;
     launches[g_prof.cls[i]]++;
   }
+  const bool lost = g_prof.dropped > 0;
   g_prof.used = 0;
-  return SLIMATTN_OK;
+  g_prof.dropped = 0;
+  return lost ? SLIMATTN_ECAP : SLIMATTN_OK;
 }
 
 }  // extern "C"

@@ -45,26 +45,37 @@ __device__ __forceinline__ bf16x8 stat_triples(float lse2, float dlt) {
   return w;
 }
 
-// Prepass: the statistics of every row and head (launches whose dQ kernel does not compute them itself).
+// Prepass: the statistics of the query rows of the listed tiles, every head (launches whose dQ kernel does not
+// compute them itself).  grid = (tiles, kStatSplit); D / 8 lanes share a (row, head).
+constexpr int kStatSplit = 4;
 template <int D>
 __global__ __launch_bounds__(256) void stat_bf16_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dO,
-                                                        const float* __restrict__ lse, bf16x8* __restrict__ stat3, int T, int Hq) {
+                                                        const float* __restrict__ lse, bf16x8* __restrict__ stat3,
+                                                        const QItem* __restrict__ items, int T, int Hq) {
   constexpr int LPR = D / 8;                                   // lanes per (row, head)
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t rh = idx / LPR;                                // row * Hq + head
-  const bool live = rh < (int64_t)T * Hq;
-  float s = 0.f;
-  if (live) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + idx * 8);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + idx * 8);
+  const QItem it = items[blockIdx.x];
+  const int n = it.q_rows * Hq * LPR;                          // lane tasks of the tile: a multiple of LPR
+  // every lane of a group of LPR runs the same iterations (the stride is a multiple of 64), so the
+  // shuffles below always see the whole group
+  for (int e0 = blockIdx.y * 256; e0 < n; e0 += kStatSplit * 256) {
+    const int e = e0 + threadIdx.x;
+    const bool live = e < n;
+    const int rh = live ? e / LPR : 0;                         // local row * Hq + head
+    const int row = it.q_row0 + rh / Hq, h = rh % Hq;
+    float s = 0.f;
+    if (live) {
+      const size_t at = ((size_t)row * Hq + h) * D + (size_t)(e % LPR) * 8;
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + at);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(dO + at);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) s = fmaf((float)a[t], (float)b[t], s);
-  }
+      for (int t = 0; t < 8; ++t) s = fmaf((float)a[t], (float)b[t], s);
+    }
 #pragma unroll
-  for (int w = LPR / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w);
-  if (live && (idx % LPR) == 0) {
-    const size_t at = (size_t)(rh % Hq) * T + (rh / Hq);
-    stat3[at] = stat_triples(lse[at] * kLog2e, s);
+    for (int w = LPR / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w);
+    if (live && (e % LPR) == 0) {
+      const size_t at = (size_t)h * T + row;
+      stat3[at] = stat_triples(lse[at] * kLog2e, s);
+    }
   }
 }
 
@@ -318,17 +329,17 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 int dq_q_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kDqBQ; }
 int dkdv_kv_tile(int dtype, int) { return dtype == SLIMATTN_F32 ? 64 : kSplitTileRows[0]; }   // bf16: the dK/dV kernel's 256 key rows per block
 
-int launch_bwd_stat_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, void* stat3) {
+int launch_bwd_stat_bf16(const LaunchCtx& c, const void* o, const void* dO, const float* lse, void* stat3, const QItem* items,
+                         int n_items) {
+  if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
-  const int64_t n = c.T * p.n_q_heads * (p.head_dim / 8);
-  if (n == 0) return 0;
-  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  const dim3 grid((unsigned)n_items, kStatSplit), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(stat_bf16_kernel<128>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse,
-                       (bf16x8*)stat3, (int)c.T, p.n_q_heads);
+                       (bf16x8*)stat3, items, (int)c.T, p.n_q_heads);
   else
     hipLaunchKernelGGL(stat_bf16_kernel<64>, grid, block, 0, (hipStream_t)c.stream, (const bf16*)o, (const bf16*)dO, lse,
-                       (bf16x8*)stat3, (int)c.T, p.n_q_heads);
+                       (bf16x8*)stat3, items, (int)c.T, p.n_q_heads);
   return (int)hipGetLastError();
 }
 

@@ -96,7 +96,8 @@ struct LaunchCtx {
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t as int.
 int launch_fwd_f32(const LaunchCtx&, const float* q, const float* k, const float* v, float* o, float* lse,
                    const QItem* items, int n_items);
-int launch_bwd_delta_f32(const LaunchCtx&, const float* o, const float* dO, float* delta);
+// delta = rowsum(dO * O) for the rows of the listed query tiles
+int launch_bwd_delta_f32(const LaunchCtx&, const float* o, const float* dO, float* delta, const QItem* items, int n_items);
 int launch_bwd_dq_f32(const LaunchCtx&, const float* q, const float* k, const float* v, const float* dO, const float* lse,
                       const float* delta, float* dQ, const QItem* items, int n_items);
 int launch_bwd_dkdv_f32(const LaunchCtx&, const float* q, const float* k, const float* v, const float* dO, const float* lse,
@@ -110,11 +111,12 @@ int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* 
 // even group sizes at head dim 128: one wave per SIMD, two heads per wave (fwd_wide_bf16.hip); same arguments
 int launch_fwd_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                          const QItem* items, int n_items);
-// the bf16 backward kernels take the row statistic in log2 units (lse2 = lse * log2 e, written by the prepass)
 // Row statistics of the bf16 backward (-lse*log2e and -delta = -dO.O per row and head, as bf16 triples):
 // either the dQ kernel computes and stores them for the rows it owns (own_stats != 0; `o`, `lse` read), or
-// the prepass below has stored them for every row and the dQ kernel reads them (own_stats == 0).
-int launch_bwd_stat_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, void* stat3);
+// the prepass below has stored them for the rows of the same query tiles and the dQ kernel reads them
+// (own_stats == 0).  Either way only rows of the launch scope are read.
+int launch_bwd_stat_bf16(const LaunchCtx&, const void* o, const void* dO, const float* lse, void* stat3, const QItem* items,
+                         int n_items);
 int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* o,
                        const float* lse, void* stat3, int own_stats, void* dQ, const QItem* items, int n_items);
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments

@@ -79,18 +79,21 @@ __global__ __launch_bounds__(kRowsF32) void fwd_f32_kernel(const float* __restri
   }
 }
 
+// delta = rowsum(dO * O) for the query rows of the listed tiles and every head: one block per tile.
 template <int D>
 __global__ __launch_bounds__(256) void delta_f32_kernel(const float* __restrict__ o, const float* __restrict__ dO,
-                                                        float* __restrict__ delta, int T, int Hq) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over T*Hq
-  if (idx >= (int64_t)T * Hq) return;
-  const int row = (int)(idx / Hq), h = (int)(idx % Hq);
-  const float* a = o + idx * D;
-  const float* b = dO + idx * D;
-  float s = 0.f;
+                                                        float* __restrict__ delta, const QItem* __restrict__ items, int T,
+                                                        int Hq) {
+  const QItem it = items[blockIdx.x];
+  for (int e = threadIdx.x; e < it.q_rows * Hq; e += 256) {
+    const int row = it.q_row0 + e / Hq, h = e % Hq;
+    const float* a = o + ((size_t)row * Hq + h) * D;
+    const float* b = dO + ((size_t)row * Hq + h) * D;
+    float s = 0.f;
 #pragma unroll
-  for (int c = 0; c < D; ++c) s = fmaf(a[c], b[c], s);
-  delta[(size_t)h * T + row] = s;
+    for (int c = 0; c < D; ++c) s = fmaf(a[c], b[c], s);
+    delta[(size_t)h * T + row] = s;
+  }
 }
 
 template <int D>
@@ -255,12 +258,11 @@ int launch_fwd_f32(const LaunchCtx& c, const float* q, const float* k, const flo
   return (int)hipGetLastError();
 }
 
-int launch_bwd_delta_f32(const LaunchCtx& c, const float* o, const float* dO, float* delta) {
+int launch_bwd_delta_f32(const LaunchCtx& c, const float* o, const float* dO, float* delta, const QItem* items, int n_items) {
+  if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
-  const int64_t n = c.T * p.n_q_heads;
-  if (n == 0) return 0;
-  DISPATCH_D(p.head_dim, hipLaunchKernelGGL(delta_f32_kernel<D>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                                            (hipStream_t)c.stream, o, dO, delta, (int)c.T, p.n_q_heads));
+  DISPATCH_D(p.head_dim, hipLaunchKernelGGL(delta_f32_kernel<D>, dim3((unsigned)n_items), dim3(256), 0,
+                                            (hipStream_t)c.stream, o, dO, delta, items, (int)c.T, p.n_q_heads));
   return (int)hipGetLastError();
 }
 

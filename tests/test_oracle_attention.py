@@ -200,3 +200,7 @@ def test_sampled_rows_match_full():
     keys = np.array([40, 41, 90, 109])
     sdk, sdv = A.dkdv_rows(q, k, v, do, cu, scale, 1, 1, keys, block=16)
     assert np.allclose(sdk, dk[keys, 1], atol=1e-12) and np.allclose(sdv, dv[keys, 1], atol=1e-12)
+    # key rows away from the sample's start: the statistics are then only computed from the first of them on
+    for keys in (np.array([93, 109]), np.array([109]), np.array([77, 78, 79])):
+        sdk, sdv = A.dkdv_rows(q, k, v, do, cu, scale, 1, 0, keys, block=16)
+        assert np.allclose(sdk, dk[keys, 0], atol=1e-12) and np.allclose(sdv, dv[keys, 0], atol=1e-12)
