@@ -40,6 +40,7 @@ extern "C" {
 #define SLIMATTN_ECAP    -3   /* an output array is too small */
 #define SLIMATTN_EHIP    -4   /* a HIP call failed; code via slimattn_last_hip_error() */
 #define SLIMATTN_ENOMEM  -5   /* host allocation failed */
+#define SLIMATTN_ESCRATCH -6  /* slimattn_bwd_static: the pack needs more scratch than the built-in array holds */
 
 #define SLIMATTN_F32   0      /* q,k,v,o,dO,dQ,dK,dV are float; all arithmetic fp32 */
 #define SLIMATTN_BF16  1      /* tensors are bf16; products on bf16 MFMA, fp32 accumulation and softmax */
@@ -183,6 +184,21 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
 int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* dO, const slimattn_tables* t, void* dQ, void* dK,
                  void* dV, void* workspace, void* stream);
+
+/* For callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same computation, arguments,
+ * unit ranges and flags as slimattn_bwd, with the workspace taken from an array built into the library
+ * (SLIMATTN_STATIC_SCRATCH_BYTES of device memory per GPU the library runs on, held until the process
+ * ends; its address is looked up once per device, by slimattn_tables_create or by the first call).  The call
+ * allocates nothing and frees nothing.  SLIMATTN_ESCRATCH when slimattn_bwd_workspace_bytes() for this
+ * pack exceeds the array (nothing is launched).  Every call on a GPU uses that GPU's one array, which keeps
+ * what the last call left: a call with unit_lo == 0 clears what must start at zero, as slimattn_bwd does,
+ * and calls that overlap in time on one GPU (two streams, two threads) race on it -- serialise them.  A
+ * unit list split over several calls must not be interleaved with calls for another pack. */
+#define SLIMATTN_STATIC_SCRATCH_BYTES (64u << 20)
+int slimattn_bwd_static(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o,
+                        const float* lse, const void* dO, const slimattn_tables* t, void* dQ, void* dK,
+                        void* dV, void* stream);
 
 /* ---- measurement aid --------------------------------------------------------------------------- */
 

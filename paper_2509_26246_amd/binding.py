@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
     "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
-    "slimattn_bwd", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
+    "slimattn_bwd", "slimattn_bwd_static", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
 KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "finalize", "fill"]
 
@@ -74,6 +74,7 @@ def load_library():
     lib.slimattn_bwd_workspace_bytes.restype = C.c_size_t
     lib.slimattn_fwd.argtypes = [C.POINTER(_Params), vp, vp, vp, vp, vp, vp, vp]
     lib.slimattn_bwd.argtypes = [C.POINTER(_Params)] + [vp] * 12
+    lib.slimattn_bwd_static.argtypes = [C.POINTER(_Params)] + [vp] * 11
     lib.slimattn_strerror.argtypes = [C.c_int]
     lib.slimattn_strerror.restype = C.c_char_p
     lib.slimattn_last_hip_error.restype = C.c_int
@@ -248,6 +249,22 @@ def bwd(q, k, v, o, lse, dO, tables: Tables, dQ, dK, dV, workspace, *, n_q_heads
     if rc != 0:
         extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
         raise SlimAttnError(rc, "slimattn_bwd", extra)
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def bwd_static(q, k, v, o, lse, dO, tables: Tables, dQ, dK, dV, *, n_q_heads: int, n_kv_heads: int, head_dim: int,
+               dtype: int, scale: float, unit_lo: int = 0, unit_hi: int = -1, flags: int = 0,
+               stream: Optional[int] = None) -> None:
+    """slimattn_bwd_static: slimattn_bwd with the library's built-in scratch array as workspace."""
+    lib = load_library()
+    prm = _params(tables.total_tokens, n_q_heads, n_kv_heads, head_dim, dtype, scale, unit_lo, unit_hi, flags)
+    rc = lib.slimattn_bwd_static(C.byref(prm), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), tables.handle,
+                                 _ptr(dQ), _ptr(dK), _ptr(dV), stream)
+    if rc != 0:
+        extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
+        raise SlimAttnError(rc, "slimattn_bwd_static", extra)
 
 
 def profile_enable(max_launches: int) -> None:

@@ -2,14 +2,41 @@
 // No device allocation and no synchronisation happens here.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
+
+// Built-in scratch for slimattn_bwd_static: one array per GPU the library runs on, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and fills get the
+// device address looked up once per device (each device has its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[SLIMATTN_STATIC_SCRATCH_BYTES];
 
 namespace slimattn {
 int& last_hip_error();
 
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up at the first call on that device).
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { last_hip_error() = (int)e; return SLIMATTN_EHIP; }
+  if (dev < 0 || dev >= kMaxDevices) return SLIMATTN_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) { last_hip_error() = (int)e; return SLIMATTN_EHIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SLIMATTN_OK;
+}
 
 bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -65,6 +92,12 @@ int timed(int cls, void* stream, F&& launch) {
 }
 
 }  // namespace
+
+int prepare_static_scratch() {
+  void* p = nullptr;
+  return static_scratch(&p);
+}
+
 }  // namespace slimattn
 
 using namespace slimattn;
@@ -218,6 +251,18 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     }));
   }
   return rc;
+}
+
+int slimattn_bwd_static(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                        const void* dO, const slimattn_tables* t, void* dQ, void* dK, void* dV, void* stream) {
+  if (!p || !t) return SLIMATTN_EINVAL;
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->head_dim < 1) return SLIMATTN_EINVAL;
+  const size_t need = slimattn_bwd_workspace_bytes(t, p->n_q_heads, p->n_kv_heads, p->head_dim);
+  if (need == 0 || need > (size_t)SLIMATTN_STATIC_SCRATCH_BYTES) return SLIMATTN_ESCRATCH;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != SLIMATTN_OK) return rc;
+  return slimattn_bwd(p, q, k, v, o, lse, dO, t, dQ, dK, dV, ws, stream);
 }
 
 int slimattn_profile_enable(int32_t max_launches) {

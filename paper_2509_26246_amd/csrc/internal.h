@@ -129,6 +129,10 @@ int launch_bwd_reduce_bf16(const LaunchCtx&, const float* parts, float* acc_dk, 
                            const KvReduce* items, int n_items, int load_acc, int store_final, int tile_rows);
 int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);
 
+// Looks up the built-in scratch array of slimattn_bwd_static on the current device (so that the first such call
+// finds it ready); returns a SLIMATTN_* code.
+int prepare_static_scratch();
+
 // Tile sizes each kernel family uses (must be one of kTileSizes).
 int fwd_q_tile(int dtype, int head_dim);
 int dq_q_tile(int dtype, int head_dim);

@@ -228,6 +228,7 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     }
     blob.resize(align_up(blob.size()) + 256);
     hipError_t e = hipGetDevice(&t->device);
+    if (e == hipSuccess) (void)prepare_static_scratch();    // set-up for slimattn_bwd_static on this device; its own call reports a failure
     if (e == hipSuccess) e = hipMalloc(&t->d_blob, blob.size());
     if (e == hipSuccess) e = hipMemcpy(t->d_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
