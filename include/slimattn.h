@@ -123,7 +123,9 @@ int slimattn_build_units(const int32_t* cu, int32_t n, const slimattn_slice* sli
                          const slimattn_policy* policy, int32_t* unit_ptr, int32_t* unit_slices,
                          int32_t cap_units, int32_t* n_units);
 
-/* Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear
+/* Checks tables against the rules of the paper's PackFlow Pipeline Parallelism Scheduling section (slice order
+ * within a sample preserved in the forward pass, backward first-in last-out) and of the MicroPack definition
+ * (SlimPack System).  Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear
  * in ascending order in the table, are non-empty and tile [0, L) exactly; kv_start/kv_len agree
  * with cu; unit_ptr is a valid CSR over unit_slices; every slice is in exactly one unit.
  * With SLIMATTN_CHECK_ORDER in `mode`: along a sample the unit index never decreases with the
@@ -142,7 +144,8 @@ int64_t slimattn_flops_bwd(int64_t pairs, int32_t head_dim, int32_t n_q_heads);
 
 /* ---- tables on the device -------------------------------------------------------------------- */
 
-/* Validates (structural rules, both lists), derives the private tile work-lists and copies
+/* The device-side form of the paper's scheduling input (SlimPack System: MicroPacks as lists of slices;
+ * Asymmetric Partition: one list per pass).  Validates (structural rules, both lists), derives the private tile work-lists and copies
  * everything to the current device with one synchronous upload.  All inputs HOST; they are copied.
  * *out receives a handle to free with slimattn_tables_destroy.  ETABLE / EHIP / ENOMEM. */
 int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
@@ -157,33 +160,51 @@ void slimattn_tables_destroy(slimattn_tables* t);
 int64_t slimattn_tables_count(const slimattn_tables* t, int what);
 
 /* Bytes of DEVICE scratch slimattn_bwd needs (fp32 dK/dV accumulators, the per-row statistics in
- * fp32 and as bf16 triples, partial tiles of divided key tiles). */
+ * fp32 and as bf16 triples, partial tiles of divided key tiles).  Its contents need no initialisation. */
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t n_q_heads, int32_t n_kv_heads,
                                     int32_t head_dim);
 
 /* ---- compute ------------------------------------------------------------------------------- */
 
-/* Forward over units [unit_lo, unit_hi) of the forward list: for every query row i of every slice
- * in those units and every head, S_ij = scale * q_i . k_j over the sample's keys j <= i,
- * lse_i = log sum_j exp S_ij, o_i = sum_j exp(S_ij - lse_i) v_j.  Rows of slices outside the unit
- * range are not written.  q, k, v DEVICE (read), o, lse DEVICE (written), 16-byte aligned.
+/* Forward over units [unit_lo, unit_hi) of the forward list (paper: PackFlow Pipeline Parallelism
+ * Scheduling, slice-level causal attention with a KV cache): for every query row i of every slice in
+ * those units and every head, S_ij = scale * q_i . k_j over the sample's keys j <= i,
+ * lse_i = log sum_j exp S_ij, o_i = sum_j exp(S_ij - lse_i) v_j.
+ * Incremental use: the call reads the q rows of the range's slices and, per sample, the k/v rows from the
+ * sample's start to the last of those rows -- nothing else; rows of other units may hold anything (their
+ * K/V need not exist yet), and o/lse rows of slices outside the range are not written.  A runtime can
+ * therefore call it one unit at a time as K/V arrive slice by slice.
+ * q, k, v DEVICE (read), o, lse DEVICE (written), 16-byte aligned.
  * stream: a hipStream_t (NULL = default stream).  Allocates nothing, does not synchronise. */
 int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v,
                  const slimattn_tables* t, void* o, float* lse, void* stream);
 
 /* Backward over units [unit_lo, unit_hi) of the backward list, with the scores recomputed from q, k
- * and lse: P_ij = exp(S_ij - lse_i), dP_ij = dO_i . v_j, delta_i = dO_i . o_i,
- * dS_ij = P_ij (dP_ij - delta_i); dQ_i = scale sum_j dS_ij k_j for the rows of the range's slices;
- * dK_j += scale sum_i dS_ij q_i and dV_j += sum_i P_ij dO_i over those rows i >= j and over the
- * query heads of j's group, accumulated in fp32 in `workspace` in a fixed order (no float
- * atomics; bitwise repeatable).  A call with unit_lo == 0 clears the accumulators first; the
- * call whose unit_hi reaches the end of the list converts them into dK, dV.  A caller that
- * splits the list over several calls passes the same workspace to each, in list order.
+ * and lse (paper: Asymmetric Cost Profile -- the recomputation is why backward costs 2.5 x forward;
+ * Asymmetric Partition -- hence a unit list of its own): P_ij = exp(S_ij - lse_i), dP_ij = dO_i . v_j,
+ * delta_i = dO_i . o_i, dS_ij = P_ij (dP_ij - delta_i); dQ_i = scale sum_j dS_ij k_j for the rows of the
+ * range's slices; dK_j += scale sum_i dS_ij q_i and dV_j += sum_i P_ij dO_i over those rows i >= j and
+ * over the query heads of j's group, in a fixed order (no float atomics; bitwise repeatable).
+ * A key row collects from every later slice of its sample (paper: DAG-based pipeline representation,
+ * inter-slice dependencies), i.e. possibly from several units.  Units must be run in list order, each
+ * exactly once, over one or several calls that share `workspace`: the first unit that reaches a key row
+ * starts its sum (nothing has to be cleared beforehand), later ones continue it in fp32 in the workspace, and
+ * the last one writes dK/dV in the output type -- so a row's gradient is final as soon as its last
+ * contributor has run (slimattn_bwd_released_rows), not only at the end of the list.
+ * Incremental use: the call reads q, dO, o, lse rows of the range's slices and the k/v rows of their
+ * samples up to those rows -- nothing else; dO, o, lse of other units may hold anything.
  * q, k, v, o, lse, dO DEVICE (read); dQ, dK, dV DEVICE (written); workspace DEVICE of at least
  * slimattn_bwd_workspace_bytes().  Allocates nothing, does not synchronise. */
 int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* dO, const slimattn_tables* t, void* dQ, void* dK,
                  void* dV, void* workspace, void* stream);
+
+/* Key rows whose dK/dV become final with backward unit `unit` (when the units before it have run): ranges
+ * [ranges[2i], ranges[2i+1]) of global token indices, ascending, n_ranges of them -- per sample, the rows
+ * between the last query row any later unit holds and the last query row this unit holds (paper: Memory
+ * footprint simulation -- KV gradients are managed per slice).  Over all units the ranges partition
+ * [0, T).  HOST arrays; ECAP if cap < n_ranges (n_ranges is still set). */
+int slimattn_bwd_released_rows(const slimattn_tables* t, int32_t unit, int32_t* ranges, int32_t cap, int32_t* n_ranges);
 
 /* For callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
  * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same computation, arguments,
@@ -207,8 +228,8 @@ int slimattn_bwd_static(const slimattn_params* p, const void* q, const void* k, 
 #define SLIMATTN_K_DELTA     1
 #define SLIMATTN_K_DQ        2
 #define SLIMATTN_K_DKDV      3
-#define SLIMATTN_K_FINALIZE  4
-#define SLIMATTN_K_FILL      5
+#define SLIMATTN_K_FINALIZE  4          /* the reduction of divided key tiles */
+#define SLIMATTN_K_FILL      5          /* (not launched any more; kept so that class numbers stay put) */
 #define SLIMATTN_K_COUNT     6
 
 /* Per-kernel timing for benchmarks (the paper calibrates its simulator from such primitive

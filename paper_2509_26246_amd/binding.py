@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
     "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
-    "slimattn_bwd", "slimattn_bwd_static", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
+    "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
 KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "finalize", "fill"]
 
@@ -75,6 +75,7 @@ def load_library():
     lib.slimattn_fwd.argtypes = [C.POINTER(_Params), vp, vp, vp, vp, vp, vp, vp]
     lib.slimattn_bwd.argtypes = [C.POINTER(_Params)] + [vp] * 12
     lib.slimattn_bwd_static.argtypes = [C.POINTER(_Params)] + [vp] * 11
+    lib.slimattn_bwd_released_rows.argtypes = [vp, C.c_int32, i32p, C.c_int32, i32p]
     lib.slimattn_strerror.argtypes = [C.c_int]
     lib.slimattn_strerror.restype = C.c_char_p
     lib.slimattn_last_hip_error.restype = C.c_int
@@ -249,6 +250,20 @@ def bwd(q, k, v, o, lse, dO, tables: Tables, dQ, dK, dV, workspace, *, n_q_heads
     if rc != 0:
         extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
         raise SlimAttnError(rc, "slimattn_bwd", extra)
+
+
+def bwd_released_rows(tables: Tables, unit: int) -> np.ndarray:
+    """[n, 2] array of key-row ranges whose dK/dV become final with backward unit `unit`."""
+    lib = load_library()
+    n = C.c_int32(0)
+    rc = lib.slimattn_bwd_released_rows(tables.handle, unit, None, 0, C.byref(n))
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_bwd_released_rows")
+    out = np.zeros((max(n.value, 1), 2), np.int32)
+    rc = lib.slimattn_bwd_released_rows(tables.handle, unit, _p(out), n.value, C.byref(n))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_bwd_released_rows")
+    return out[:n.value].copy()
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

@@ -187,27 +187,24 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
                  : launch_bwd_dq_bf16(ctx, q, k, v, dO, o, lse, stat3, own_stats ? 1 : 0, dQ, items, n);
     });
   };
-  auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs, int load_acc, int store_final) -> int {
+  auto run_dkdv = [&](const KvItem* items, int n, const Seg* segs) -> int {
     return timed(SLIMATTN_K_DKDV, stream, [&] {
       return f32 ? launch_bwd_dkdv_f32(ctx, (const float*)q, (const float*)k, (const float*)v, (const float*)dO, lse,
-                                       delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs, load_acc,
-                                       store_final)
-                 : launch_bwd_dkdv_wide_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, load_acc, store_final,
-                                             parts);
+                                       delta, acc_dk, acc_dv, (float*)dK, (float*)dV, items, n, segs)
+                 : launch_bwd_dkdv_wide_bf16(ctx, q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n, segs, parts);
     });
   };
   // bf16: the key-tile list in which heavy tiles are divided among several blocks, followed by the
   // launch that adds the parts up (a scope without divided tiles has an empty reduction list)
-  auto run_dkdv_split = [&](const ScopeLists& L, const DeviceLists& D, int u, int load_acc, int store_final) -> int {
+  auto run_dkdv_split = [&](const ScopeLists& L, const DeviceLists& D, int u) -> int {
     const int tile_rows = dkdv_kv_tile(p->dtype, p->head_dim), ti = split_tile_index(tile_rows);
     const int a = L.split_off[ti][sc][u], b = L.split_off[ti][sc][u + 1];
-    int e = run_dkdv(D.split_items[ti][sc] + a, b - a, D.segs, load_acc, store_final);
+    int e = run_dkdv(D.split_items[ti][sc] + a, b - a, D.segs);
     if (e != 0) return e;
     const int ra = L.reduce_off[ti][sc][u], rb = L.reduce_off[ti][sc][u + 1];
     if (rb == ra) return 0;
     return timed(SLIMATTN_K_FINALIZE, stream, [&] {
-      return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[ti][sc] + ra, rb - ra, load_acc,
-                                    store_final, tile_rows);
+      return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[ti][sc] + ra, rb - ra, tile_rows);
     });
   };
 
@@ -216,40 +213,31 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
     // writes dK/dV directly; the fp32 accumulators in the workspace are not touched.
     rc = hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
     if (rc != SLIMATTN_OK) return rc;
-    return hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs, 0, 1)
-                      : run_dkdv_split(t->fused, t->d_fused, 0, 0, 1));
+    return hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs)
+                      : run_dkdv_split(t->fused, t->d_fused, 0));
   }
 
   const auto& qoff = t->per_unit[1].q_off[zq];
   const auto& koff = t->per_unit[1].kv_off[zk];
-  if (lo == 0) {
-    rc = hip_rc(timed(SLIMATTN_K_FILL, stream, [&] { return launch_fill_zero(ctx, acc_dk, (int64_t)(2 * acc_elems)); }));
-    if (rc != SLIMATTN_OK) return rc;
-  }
   if (!per_unit) {
     rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[lo], qoff[hi] - qoff[lo]));
     if (rc != SLIMATTN_OK) return rc;
   }
   for (int u = lo; u < hi; ++u) {
-    // Units run one after another on the stream; each adds its queries' contributions to the
-    // accumulators of every key tile of the prefix it sees (read-modify-write by the tile's
-    // single owner), so the summation order is the unit order.
+    // Units run one after another on the stream; each adds its queries' contributions to every key tile of the
+    // prefix it sees.  The tile's single owner block continues from the fp32 accumulator an earlier unit left
+    // (the tile's first unit starts from zero, so nothing has to be cleared) and the tile's last unit writes
+    // dK/dV themselves: the summation order is the unit order, and a tile is released as soon as it is complete.
     g_prof.cur_unit = u;
     if (per_unit) {
       rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));
       if (rc != SLIMATTN_OK) return rc;
     }
-    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs, 1, 0)
-                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u, 1, 0));
+    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs)
+                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u));
     if (rc != SLIMATTN_OK) return rc;
   }
   g_prof.cur_unit = -1;
-  if (hi == n_units) {
-    rc = hip_rc(timed(SLIMATTN_K_FINALIZE, stream, [&] {
-      return f32 ? launch_finalize_f32(ctx, acc_dk, acc_dv, (float*)dK, (float*)dV)
-                 : launch_finalize_bf16(ctx, acc_dk, acc_dv, dK, dV);
-    }));
-  }
   return rc;
 }
 

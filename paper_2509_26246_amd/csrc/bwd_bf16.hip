@@ -5,11 +5,12 @@
 // the forward).  Two kernels:
 //   dQ    : a block owns 128 query rows of one head and walks the keys it can see;
 //           S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T.
-//   dK/dV : a block owns 128 key rows of one KV head and walks every query row of the launch
-//           scope at or after them, for every query head of the group, in a fixed order;
-//           S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.  A key tile's gradient is thus
-//           summed by its single owner (the paper's "KV gradients from subsequent slices"),
-//           with no float atomics; across launches the owner continues from fp32 accumulators.
+//   dK/dV : (dkdv_wide_bf16.hip) a block owns 256 key rows of one KV head and walks every query row of
+//           the launch scope at or after them, for every query head of the group, in a fixed order;
+//           S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.  A key tile's gradient, which collects
+//           from every later slice of its sample (the inter-slice dependency of the backward pass in the
+//           paper's DAG simulator section), is thus summed by its single owner, with no float atomics;
+//           across launches the owner continues from fp32 accumulators.
 // In both, the lane layout of the first products' accumulators is, unchanged, the B operand of
 // the last products; the matching A operands (K^T, dO^T, Q^T) come from LDS transpose loads.
 #include <hip/hip_runtime.h>
@@ -178,8 +179,8 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
   const int q0w = it.q_row0 + 32 * wave, my_row = q0w + l32, q_end = it.q_row0 + it.q_rows;
   const int ld_row = min(my_row, T - 1);
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
-  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
-  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, q_end, tid);
+  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, q_end, tid);
   stage_tile<D, kDqBK, 256>(lds, srcK, 0, tid);
   stage_tile<D, kDqBK, 256>(lds + kTileBytes, srcV, 0, tid);
 
@@ -290,7 +291,7 @@ template <int D>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ parts, float* __restrict__ acc_dk,
                                                            float* __restrict__ acc_dv, bf16* __restrict__ dK,
                                                            bf16* __restrict__ dV, const KvReduce* __restrict__ items,
-                                                           int Hkv, int load_acc, int store_final, int tile_rows) {
+                                                           int Hkv, int tile_rows) {
   const KvReduce it = items[blockIdx.x / Hkv];
   const int hk = blockIdx.x % Hkv;
   const int kTile = tile_rows * D;                     // elements of one partial dK (or dV) tile
@@ -302,6 +303,7 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restri
       sum += *reinterpret_cast<const floatx4*>(parts + ((size_t)(it.first_slot + p) * Hkv + hk) * (2 * kTile) + e);
     const size_t off = ((size_t)(it.kv_row0 + r) * Hkv + hk) * D + c;
     float* acc = which ? acc_dv : acc_dk;
+    const bool load_acc = it.kv_row0 + r < it.load_until, store_final = it.kv_row0 + r >= it.final_from;
     if (load_acc) sum += *reinterpret_cast<const floatx4*>(acc + off);
     if (store_final) {
       bf16x4 w;
@@ -312,16 +314,6 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restri
       *reinterpret_cast<floatx4*>(acc + off) = sum;
     }
   }
-}
-
-__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ a, bf16* __restrict__ b, int64_t n4) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n4) return;
-  const floatx4 x = reinterpret_cast<const floatx4*>(a)[i];
-  bf16x4 w;
-#pragma unroll
-  for (int t = 0; t < 4; ++t) w[t] = (bf16)x[t];
-  reinterpret_cast<bf16x4*>(b)[i] = w;
 }
 
 }  // namespace
@@ -371,26 +363,16 @@ int launch_bwd_dq_bf16(const LaunchCtx& c, const void* q, const void* k, const v
 }
 
 int launch_bwd_reduce_bf16(const LaunchCtx& c, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
-                           const KvReduce* items, int n_items, int load_acc, int store_final, int tile_rows) {
+                           const KvReduce* items, int n_items, int tile_rows) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(reduce_parts_kernel<128>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
-                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final, tile_rows);
+                       (bf16*)dV, items, p.n_kv_heads, tile_rows);
   else
     hipLaunchKernelGGL(reduce_parts_kernel<64>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
-                       (bf16*)dV, items, p.n_kv_heads, load_acc, store_final, tile_rows);
-  return (int)hipGetLastError();
-}
-
-int launch_finalize_bf16(const LaunchCtx& c, const float* acc_dk, const float* acc_dv, void* dK, void* dV) {
-  const slimattn_params& p = *c.p;
-  const int64_t n4 = c.T * p.n_kv_heads * p.head_dim / 4;
-  if (n4 == 0) return 0;
-  const dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
-  hipLaunchKernelGGL(cast_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, acc_dk, (bf16*)dK, n4);
-  hipLaunchKernelGGL(cast_bf16_kernel, grid, block, 0, (hipStream_t)c.stream, acc_dv, (bf16*)dV, n4);
+                       (bf16*)dV, items, p.n_kv_heads, tile_rows);
   return (int)hipGetLastError();
 }
 

@@ -265,13 +265,16 @@ __device__ __forceinline__ void dkdv_wide_block(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv,
     bf16* __restrict__ dK, bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs,
-    int T, int Hq, int Hkv, float scale, int load_acc, int store_final, float* __restrict__ parts) {
+    int T, int Hq, int Hkv, float scale, float* __restrict__ parts) {
   __shared__ __attribute__((aligned(1024))) char smem[kVBase<D> + kVBytes<D>];   // three [Q, dO] stages, then the V tile
 
   const int g = Hq / Hkv;
   const int item_idx = blockIdx.x / Hkv, hk = blockIdx.x % Hkv;
   if (item_idx >= n_items) return;
   const KvItem it = items[item_idx];
+  // where the rows' sums come from and go to: rows below load_until continue the partial sum an earlier unit left in
+  // the fp32 accumulators; rows from final_from on get no later contribution and are written as dK/dV in the
+  // output type, the others into the accumulators
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int kv0w = it.kv_row0 + 64 * wave, kv_end = it.kv_row0 + it.kv_rows;
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
@@ -317,10 +320,21 @@ __device__ __forceinline__ void dkdv_wide_block(
     return ok;
   };
 
-  const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);
-  const TileSource srcDO = make_tile_source<D, 256>(dO, it.kv_row0, Hq, 0, T, tid);
+  // Q and dO rows come through descriptors based at the tile's first key row (head 0) whose range ends with the
+  // query run of the step being staged: the rows of a step that lie past the end of its run (they belong to
+  // another unit, whose dO may not exist yet, or to the next sample) read as zeros and add nothing to the
+  // gradient products, whatever the memory holds.
+  const bf16* const q_base = q + (size_t)it.kv_row0 * Hq * D;
+  const bf16* const do_base = dO + (size_t)it.kv_row0 * Hq * D;
+  auto run_range = [&](const Step& d) -> int { return (d.hi - it.kv_row0) * (Hq * kRowBytes<D>); };   // bytes up to the run's end
+  auto rsrc_of = [&](const bf16* base, int bytes) -> __amdgpu_buffer_rsrc_t {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes, 0x00020000);
+  };
+  const TileSource srcQ = make_tile_source<D, 256>(q, it.kv_row0, Hq, 0, T, tid);    // (voff, row_bytes; its range is replaced per step)
   auto stage = [&](const Step& d, int st) {             // a step's Q and dO tiles straight into LDS
-    TileSource a = srcQ, b = srcDO;
+    TileSource a = srcQ, b = srcQ;
+    a.rsrc = rsrc_of(q_base, run_range(d));
+    b.rsrc = rsrc_of(do_base, run_range(d));
     a.voff += d.head * kRowBytes<D>;
     b.voff += d.head * kRowBytes<D>;
     stage_tile<D, kQStep, 256>(lds + st * kStageBytes<D>, a, d.i0 - it.kv_row0, tid);
@@ -346,7 +360,7 @@ __device__ __forceinline__ void dkdv_wide_block(
   const uintx4 ones_l = {one2, one1, 0u, 0u}, ones_d = {0u, 0u, one2, one1};
   bool have_s = true;
   {
-    const TileSource srcV = make_tile_source<D, 256>(v, it.kv_row0, Hkv, hk, T, tid);
+    const TileSource srcV = make_tile_source<D, 256>(v, it.kv_row0, Hkv, hk, kv_end, tid);
     stage_tile<D, kKeys, 256>(lds + kVBase<D>, srcV, 0, tid);
   }
   bf16x8 kf[2][kNKS<D>];
@@ -418,7 +432,7 @@ __device__ __forceinline__ void dkdv_wide_block(
     constexpr int kSlotGrad = 4 * (kNKS<D> - 2);
     constexpr int kPasses = kTileBytes<D> / 4096;         // staging loads per tile (256 threads x 16 bytes each)
     bool ok_n = false;
-    int stat_off = 0;
+    int stat_off = 0, range_n = 0;
     auto between = [&](auto kc) {                       // piece k of the bookkeeping, behind score product k
       constexpr int k = decltype(kc)::value;
       if constexpr (k < kNDB<D>) { lds_ptr_add(pqt[k][0], dt_pend); lds_ptr_add(pqt[k][1], dt_pend); }
@@ -430,14 +444,15 @@ __device__ __forceinline__ void dkdv_wide_block(
       if constexpr (k == kSlotAddr) {
         voff_n = srcQ.voff + d_n.head * kRowBytes<D>;   // the Q and dO sources differ in their descriptors only
         soff_n = __builtin_amdgcn_readfirstlane((d_n.i0 - it.kv_row0) * srcQ.row_bytes);
-        asm volatile("" : "+v"(voff_n), "+s"(soff_n));
+        range_n = __builtin_amdgcn_readfirstlane(run_range(d_n));
+        asm volatile("" : "+v"(voff_n), "+s"(soff_n), "+s"(range_n));
       }
       if constexpr (k >= kSlotLoad && k < kSlotLoad + 2 * kPasses * kLoadStride && (k - kSlotLoad) % kLoadStride == 0) {
         // one load each: the passes of the Q tile, then of the dO tile
         constexpr int x = (k - kSlotLoad) / kLoadStride, tile = x / kPasses, pass = x % kPasses;
         constexpr int kRowsPerPass = 4096 / kRowBytes<D>;
         // (when the walk has ended d_n still names the last step: its tile is staged once more, into a stage nobody reads)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(tile ? srcDO.rsrc : srcQ.rsrc, lds + m0_n + tile * kTileBytes<D> + pass * 4096, 16,
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_of(tile ? do_base : q_base, range_n), lds + m0_n + tile * kTileBytes<D> + pass * 4096, 16,
                                                  voff_n, soff_n + pass * kRowsPerPass * srcQ.row_bytes, 0, 0);
       }
       if constexpr (k == kSlotMask) m_n = masks(d_n);
@@ -470,7 +485,7 @@ __device__ __forceinline__ void dkdv_wide_block(
   // compiler does not know that the asm statements are matrix products): explicit wait states
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
 
-  if (it.slot < 0 && store_final && !load_acc) {
+  if (it.slot < 0 && it.final_from <= it.kv_row0 && it.load_until <= it.kv_row0) {
     // The fused launch's case: bf16 rows of dK, then of dV, out through LDS (stages and V tile are free behind
     // the loop's last barrier; each wave uses a part of its own).  A lane owns a row's values in pieces of 4
     // columns, and written as they stand each store instruction would touch 32 rows with 16 bytes each;
@@ -522,6 +537,7 @@ __device__ __forceinline__ void dkdv_wide_block(
         }
     } else if (my_key < kv_end) {
       const size_t base = ((size_t)my_key * Hkv + hk) * D;
+      const bool load_acc = my_key < it.load_until, store_final = my_key >= it.final_from;
 #pragma unroll
       for (int db = 0; db < kNDB<D>; ++db)
 #pragma unroll
@@ -554,33 +570,33 @@ __global__ __launch_bounds__(256, 1) void dkdv_wide_bf16_kernel_d128(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv, bf16* __restrict__ dK,
     bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs, int T, int Hq, int Hkv,
-    float scale, int load_acc, int store_final, float* __restrict__ parts) {
-  dkdv_wide_block<128>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, load_acc, store_final, parts);
+    float scale, float* __restrict__ parts) {
+  dkdv_wide_block<128>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, parts);
 }
 __global__ __launch_bounds__(256, 1) void dkdv_wide_bf16_kernel_d64(
     const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v, const bf16* __restrict__ dO,
     const bf16x8* __restrict__ stat3, float* __restrict__ acc_dk, float* __restrict__ acc_dv, bf16* __restrict__ dK,
     bf16* __restrict__ dV, const KvItem* __restrict__ items, int n_items, const Seg* __restrict__ segs, int T, int Hq, int Hkv,
-    float scale, int load_acc, int store_final, float* __restrict__ parts) {
-  dkdv_wide_block<64>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, load_acc, store_final, parts);
+    float scale, float* __restrict__ parts) {
+  dkdv_wide_block<64>(q, k, v, dO, stat3, acc_dk, acc_dv, dK, dV, items, n_items, segs, T, Hq, Hkv, scale, parts);
 }
 
 }  // namespace
 
 int launch_bwd_dkdv_wide_bf16(const LaunchCtx& c, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
-                            int load_acc, int store_final, float* parts) {
+                            float* parts) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(dkdv_wide_bf16_kernel_d128, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, parts);
   else
     hipLaunchKernelGGL(dkdv_wide_bf16_kernel_d64, grid, block, 0, (hipStream_t)c.stream, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (const bf16*)dO, (const bf16x8*)stat3, acc_dk, acc_dv, (bf16*)dK, (bf16*)dV, items, n_items,
-                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final, parts);
+                       segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, parts);
   return (int)hipGetLastError();
 }
 

@@ -137,8 +137,8 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
   LDS_PTR(char) lds = (LDS_PTR(char))smem;
 
   const int n_tiles = (q_end - it.kv_start + kFwdBK - 1) / kFwdBK;
-  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
-  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, q_end, tid);
+  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, q_end, tid);
   stage_tile<D, kFwdBK, 256>(lds, srcK, 0, tid);
   stage_tile<D, kFwdBK, 256>(lds + kTileBytes, srcV, 0, tid);
 
@@ -397,8 +397,8 @@ __global__ __launch_bounds__(512, 2) void fwd_pair_bf16_kernel(const bf16* __res
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
-  const TileSource srcK = make_tile_source<D, 512>(k, it.kv_start, Hkv, hk, T, tid);
-  const TileSource srcV = make_tile_source<D, 512>(v, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcK = make_tile_source<D, 512>(k, it.kv_start, Hkv, hk, q_end, tid);
+  const TileSource srcV = make_tile_source<D, 512>(v, it.kv_start, Hkv, hk, q_end, tid);
   stage_tile<D, kFwdBK, 512>(lds, srcK, 0, tid);
   stage_tile<D, kFwdBK, 512>(lds + kTileBytes, srcV, 0, tid);
   stage_tile<D, kFwdBK, 512>(lds + kBufBytes, srcK, kFwdBK, tid);

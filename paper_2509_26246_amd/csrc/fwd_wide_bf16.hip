@@ -164,8 +164,8 @@ __device__ __forceinline__ void fwd_wide_item(const QItem it, const int hk, cons
 #pragma unroll
     for (int u = 0; u < NKS; ++u) k0[u] = *reinterpret_cast<const bf16x8*>(kp + 16 * u);
   }
-  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, T, tid);
-  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, T, tid);
+  const TileSource srcK = make_tile_source<D, 256>(k, it.kv_start, Hkv, hk, q_end, tid);
+  const TileSource srcV = make_tile_source<D, 256>(v, it.kv_start, Hkv, hk, q_end, tid);
   // K(0), K(1) and V(0) are on their way before anything waits: one memory latency per item, not one per early tile
   stage_tile<D, kKeys, 256>(lds, srcK, 0, tid);
   stage_tile<D, kKeys, 256>(lds + kTileBytes<D>, srcK, kKeys, tid);

@@ -7,9 +7,12 @@
 
 namespace slimattn {
 
-// Tile sizes for which work-lists are derived (query-tile rows / key-tile rows).
-constexpr int kNumTileSizes = 4;
-constexpr int kTileSizes[kNumTileSizes] = {32, 64, 128, 256};
+// Tile sizes for which work-lists are derived: query tiles of 64 (fp32 kernels) and 128 rows (bf16 forward,
+// dQ), key tiles of 64 (fp32) and 256 rows (bf16 dK/dV).
+constexpr int kNumTileSizes = 3;
+constexpr int kTileSizes[kNumTileSizes] = {64, 128, 256};
+inline bool is_query_tile(int rows) { return rows == 64 || rows == 128; }
+inline bool is_key_tile(int rows) { return rows == 64 || rows == 256; }
 inline int tile_index(int rows) {
   for (int i = 0; i < kNumTileSizes; ++i) if (kTileSizes[i] == rows) return i;
   return -1;
@@ -27,12 +30,23 @@ struct Seg { int32_t q_lo, q_hi; };
 // every such run and its block owns the tile's dK/dV.  slot >= 0: the item is one part of a heavy
 // tile whose query rows were divided among several blocks; it covers only its own runs and stores
 // its sums as fp32 partial tile number `slot`, which a reduction launch adds up in slot order.
-struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end, slot, pad0, pad1, pad2; };
+// load_until, final_from: where the rows' sums come from and go to (below).
+struct KvItem { int32_t kv_row0, kv_rows, seg_begin, seg_end, slot, load_until, final_from, pad; };
+
+// A key row collects from every unit of the backward list that has query rows of the sample at or after it
+// (a slice's dK/dV are complete only when all later slices have run: the paper's inter-slice dependency of
+// the backward pass).  Units run in list order, and a unit reaches the rows before the end of its last query
+// row in the sample.  So for the rows of a unit's key tile: rows below `load_until` (the furthest reach of an
+// earlier unit) continue a partial sum that unit left in the fp32 accumulators, the others start from zero
+// (nothing has to be cleared beforehand); rows from `final_from` on (the furthest reach of a later unit) get no
+// further contribution and are written as dK/dV in the output type, the others go to the accumulators.  A
+// row's gradient is thus released by its last contributor, not at the end of the list.  Whole-list scope:
+// load_until = 0, final_from = 0.
 
 // A divided key tile: partial tiles first_slot .. first_slot + n_parts - 1 are its parts.
-struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts; };
+struct KvReduce { int32_t kv_row0, kv_rows, first_slot, n_parts, load_until, final_from, pad0, pad1; };
 
-// Divided lists exist for the 128- and 256-row key tiles (the two bf16 dK/dV kernels) and four classes
+// Divided lists exist for the 256-row key tile (the bf16 dK/dV kernel) and four classes
 // of KV-head count (1, 2, 4, >= 8): a launch has items x KV heads blocks, so the fewer KV heads, the
 // fewer blocks share the work and the more a single long sample's first tiles dominate the makespan.
 constexpr int kNumSplitTiles = 1;                               // key-tile sizes for which divided lists are built
@@ -102,9 +116,7 @@ int launch_bwd_dq_f32(const LaunchCtx&, const float* q, const float* k, const fl
                       const float* delta, float* dQ, const QItem* items, int n_items);
 int launch_bwd_dkdv_f32(const LaunchCtx&, const float* q, const float* k, const float* v, const float* dO, const float* lse,
                         const float* delta, float* acc_dk, float* acc_dv, float* dK, float* dV, const KvItem* items,
-                        int n_items, const Seg* segs, int load_acc, int store_final);
-int launch_finalize_f32(const LaunchCtx&, const float* acc_dk, const float* acc_dv, float* dK, float* dV);
-int launch_fill_zero(const LaunchCtx&, float* ptr, int64_t n);
+                        int n_items, const Seg* segs);
 
 int launch_fwd_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, void* o, float* lse,
                     const QItem* items, int n_items);
@@ -122,12 +134,11 @@ int launch_bwd_dq_bf16(const LaunchCtx&, const void* q, const void* k, const voi
 // head_dim 128: one wave per SIMD, 256 key rows per block (dkdv_wide_bf16.hip); same arguments
 int launch_bwd_dkdv_wide_bf16(const LaunchCtx&, const void* q, const void* k, const void* v, const void* dO, const void* stat3,
                             float* acc_dk, float* acc_dv, void* dK, void* dV, const KvItem* items, int n_items, const Seg* segs,
-                            int load_acc, int store_final, float* parts);
+                            float* parts);
 // adds up the partial tiles (tile_rows rows each) of divided key tiles, in slot order, into dK/dV or the
 // fp32 accumulators
 int launch_bwd_reduce_bf16(const LaunchCtx&, const float* parts, float* acc_dk, float* acc_dv, void* dK, void* dV,
-                           const KvReduce* items, int n_items, int load_acc, int store_final, int tile_rows);
-int launch_finalize_bf16(const LaunchCtx&, const float* acc_dk, const float* acc_dv, void* dK, void* dV);
+                           const KvReduce* items, int n_items, int tile_rows);
 
 // Looks up the built-in scratch array of slimattn_bwd_static on the current device (so that the first such call
 // finds it ready); returns a SLIMATTN_* code.

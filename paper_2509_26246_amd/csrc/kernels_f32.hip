@@ -41,9 +41,13 @@ __global__ __launch_bounds__(kRowsF32) void fwd_f32_kernel(const float* __restri
     __syncthreads();
     for (int e = lane; e < kKeysStage * (D / 4); e += kRowsF32) {
       const int r = e / (D / 4), c4 = e % (D / 4);
-      const int jr = min(j0 + r, T - 1);
-      reinterpret_cast<float4*>(&sK[r][0])[c4] = reinterpret_cast<const float4*>(k + ((size_t)jr * Hkv + hk) * D)[c4];
-      reinterpret_cast<float4*>(&sV[r][0])[c4] = reinterpret_cast<const float4*>(v + ((size_t)jr * Hkv + hk) * D)[c4];
+      // rows from kv_end on belong to other units (their K/V may not exist yet): staged as zeros, so that
+      // their probability 0 times their value is 0 whatever the memory holds
+      const bool in = j0 + r < kv_end;
+      const int jr = min(j0 + r, kv_end - 1);
+      const float4 zero = {0.f, 0.f, 0.f, 0.f};
+      reinterpret_cast<float4*>(&sK[r][0])[c4] = in ? reinterpret_cast<const float4*>(k + ((size_t)jr * Hkv + hk) * D)[c4] : zero;
+      reinterpret_cast<float4*>(&sV[r][0])[c4] = in ? reinterpret_cast<const float4*>(v + ((size_t)jr * Hkv + hk) * D)[c4] : zero;
     }
     __syncthreads();
     float s[kKeysStage];
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(128) void dkdv_f32_kernel(const float* __restrict__
                                                        float* __restrict__ acc_dk, float* __restrict__ acc_dv,
                                                        float* __restrict__ dK, float* __restrict__ dV,
                                                        const KvItem* __restrict__ items, const Seg* __restrict__ segs, int T,
-                                                       int Hq, int Hkv, float scale, int load_acc, int store_final) {
+                                                       int Hq, int Hkv, float scale) {
   constexpr int HD = D / 2;
   __shared__ float sQ[kQStage][D];
   __shared__ float sDO[kQStage][D];
@@ -164,6 +168,9 @@ __global__ __launch_bounds__(128) void dkdv_f32_kernel(const float* __restrict__
   const int key_local = wave * 32 + (lane % 32), half = lane / 32;
   const bool live = key_local < it.kv_rows;
   const int key = min(it.kv_row0 + key_local, T - 1);
+  // an earlier unit's partial sum of this row is added (rows below load_until); rows no later unit reaches
+  // (from final_from on) are written as dK/dV, the others into the accumulators
+  const bool load_acc = key < it.load_until, store_final = key >= it.final_from;
   float kr[HD], vr[HD], dk[HD], dv[HD];
   const size_t kv_off = ((size_t)key * Hkv + hk) * D + half * HD;
 #pragma unroll
@@ -227,16 +234,6 @@ __global__ __launch_bounds__(128) void dkdv_f32_kernel(const float* __restrict__
   }
 }
 
-__global__ void copy_f32_kernel(const float* __restrict__ a, float* __restrict__ b, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) b[i] = a[i];
-}
-
-__global__ void fill_zero_kernel(float* __restrict__ p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.f;
-}
-
 #define DISPATCH_D(D_, BODY)                 \
   switch (D_) {                              \
     case 16: { constexpr int D = 16; BODY; } break;   \
@@ -278,28 +275,12 @@ int launch_bwd_dq_f32(const LaunchCtx& c, const float* q, const float* k, const 
 
 int launch_bwd_dkdv_f32(const LaunchCtx& c, const float* q, const float* k, const float* v, const float* dO,
                         const float* lse, const float* delta, float* acc_dk, float* acc_dv, float* dK, float* dV,
-                        const KvItem* items, int n_items, const Seg* segs, int load_acc, int store_final) {
+                        const KvItem* items, int n_items, const Seg* segs) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
   DISPATCH_D(p.head_dim, hipLaunchKernelGGL(dkdv_f32_kernel<D>, dim3(n_items, p.n_kv_heads), dim3(128), 0,
                                             (hipStream_t)c.stream, q, k, v, dO, lse, delta, acc_dk, acc_dv, dK, dV, items,
-                                            segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale, load_acc, store_final));
-  return (int)hipGetLastError();
-}
-
-int launch_finalize_f32(const LaunchCtx& c, const float* acc_dk, const float* acc_dv, float* dK, float* dV) {
-  const slimattn_params& p = *c.p;
-  const int64_t n = c.T * p.n_kv_heads * p.head_dim;
-  if (n == 0) return 0;
-  const unsigned blocks = (unsigned)((n + 255) / 256);
-  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)c.stream, acc_dk, dK, n);
-  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)c.stream, acc_dv, dV, n);
-  return (int)hipGetLastError();
-}
-
-int launch_fill_zero(const LaunchCtx& c, float* ptr, int64_t n) {
-  if (n == 0) return 0;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)c.stream, ptr, n);
+                                            segs, (int)c.T, p.n_q_heads, p.n_kv_heads, p.scale));
   return (int)hipGetLastError();
 }
 

@@ -261,20 +261,24 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 // ---- global -> LDS staging through buffer loads -----------------------------------------------
 // A TileSource addresses the rows of one head of a [T, H, D] bf16 tensor starting at row `row_base`
-// through a raw buffer descriptor whose range ends with the tensor: rows past the end read as
-// zeros (they are never used unmasked), so no clamping is needed, and a tile's address is a
-// per-lane constant (voff) plus a wave-uniform scalar.  The bytes from row_base to the end of
-// what a kernel touches must stay below 4 GiB (checked on the host).
+// through a raw buffer descriptor whose range ends with row `row_end` - 1: the hardware checks the
+// whole offset (per-lane part plus scalar part) against the range and answers reads of rows from
+// `row_end` on with zeros, without touching memory.  Callers put the end of what their launch
+// scope may read there -- the query tile's last row for K/V, the query run's last row for Q/dO --
+// so rows behind it (other units' rows, which may not have been produced yet, or the end of the
+// tensor) never reach a product, and no clamping code is needed; a tile's address is a per-lane
+// constant (voff) plus a wave-uniform scalar.  The bytes from row_base to row_end must stay below
+// 4 GiB (checked on the host).
 struct TileSource {
   __amdgpu_buffer_rsrc_t rsrc;
   int voff;        // this lane's byte offset within one pass of 256-byte lines
   int row_bytes;   // H * D * 2
 };
 template <int D, int NT>
-__device__ __forceinline__ TileSource make_tile_source(const bf16* base, int row_base, int H, int h, int T, int tid) {
+__device__ __forceinline__ TileSource make_tile_source(const bf16* base, int row_base, int H, int h, int row_end, int tid) {
   TileSource s;
   const size_t first = ((size_t)row_base * H + h) * D;
-  const size_t valid = ((size_t)T * H * D - first) * 2;
+  const size_t valid = ((size_t)row_end * H * D - first) * 2;
   s.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(base + first), 0, (int)(valid > 0xFFFFFFFFull ? 0xFFFFFFFFull : valid),
                                              0x00020000);
   s.row_bytes = H * D * 2;

@@ -3,10 +3,11 @@
 // The derived lists are private to the library.  A launch scope is one unit, or the whole list.
 // Inside a scope the slices of a sample that touch each other are merged into runs of query rows;
 // runs are cut into query tiles (forward, dQ) and the sample prefix they can see is cut into key
-// tiles (dK/dV: the tile's owner sums the contributions of every run that ends after it --
-// the paper's "backward pass depends on KV gradients from subsequent slices", DAG simulator
-// section).  Items are ordered heavy-first so that the hardware's in-order block dispatch acts
-// as a longest-processing-time schedule.
+// tiles (dK/dV: the tile's owner sums the contributions of every run that ends after it: a slice's
+// key/value gradients are complete only once every later slice of its sample has run -- the
+// inter-slice dependency of the backward pass in the paper's DAG simulator section).  Items are
+// ordered heavy-first so that the hardware's in-order block dispatch acts as a
+// longest-processing-time schedule.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -39,7 +40,7 @@ std::vector<Run> merge_runs(const slimattn_slice* sl, const int32_t* ids, int32_
   return out;
 }
 
-// Divided variants of one scope's 128-row key tiles.  With h KV heads a launch has items x h
+// Divided variants of one scope's 256-row key tiles.  With h KV heads a launch has items x h
 // blocks on kBlockSlots resident slots, so a tile whose query rows exceed a fraction of the
 // per-slot share W * h / kBlockSlots is cut into parts of about half a share (parts no shorter
 // than kMinPartRows).  A part is an item of
@@ -69,7 +70,7 @@ void append_split(ScopeLists& L, int ti, const std::vector<KvItem>& ki, const st
         continue;
       }
       const int64_t chunk = ((weight[x] + parts - 1) / parts + 127) / 128 * 128;
-      L.reduce_items[ti][c].push_back(KvReduce{ki[x].kv_row0, ki[x].kv_rows, slots, 0});
+      L.reduce_items[ti][c].push_back(KvReduce{ki[x].kv_row0, ki[x].kv_rows, slots, 0, ki[x].load_until, ki[x].final_from, 0, 0});
       KvReduce& red = L.reduce_items[ti][c].back();
       // walk the tile's runs, closing a part whenever it holds `chunk` rows
       int64_t have = 0;
@@ -105,15 +106,18 @@ void append_split(ScopeLists& L, int ti, const std::vector<KvItem>& ki, const st
   }
 }
 
-void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
+// `row_marks(sample)`: {load_until, final_from} of the sample's key rows for this scope.
+template <class Marks>
+void append_scope(ScopeLists& L, const std::vector<Run>& runs, Marks&& row_marks) {
   const int32_t seg_base = (int32_t)L.segs.size();
   for (const Run& r : runs) L.segs.push_back(Seg{r.q_lo, r.q_hi});
   for (int z = 0; z < kNumTileSizes; ++z) {
     const int32_t B = kTileSizes[z];
     // query tiles, heavy-first by visible prefix length
     std::vector<QItem> qi;
-    for (const Run& r : runs)
-      for (int32_t a = r.q_lo; a < r.q_hi; a += B) qi.push_back(QItem{a, std::min(B, r.q_hi - a), r.kv_start, 0});
+    if (is_query_tile(B))
+      for (const Run& r : runs)
+        for (int32_t a = r.q_lo; a < r.q_hi; a += B) qi.push_back(QItem{a, std::min(B, r.q_hi - a), r.kv_start, 0});
     std::stable_sort(qi.begin(), qi.end(), [](const QItem& a, const QItem& b) {
       return (a.q_row0 + a.q_rows - a.kv_start) > (b.q_row0 + b.q_rows - b.kv_start);
     });
@@ -122,17 +126,19 @@ void append_scope(ScopeLists& L, const std::vector<Run>& runs) {
     // key tiles: per sample, prefix [kv_start, last run's end); heavy-first by query rows at or after the tile
     std::vector<KvItem> ki;
     std::vector<int64_t> weight;
-    size_t i = 0;
+    size_t i = is_key_tile(B) ? 0 : runs.size();
     while (i < runs.size()) {
       size_t j = i;
       while (j < runs.size() && runs[j].sample == runs[i].sample) ++j;
       const int32_t kv0 = runs[i].kv_start, kv_end = runs[j - 1].q_hi;
+      const std::pair<int32_t, int32_t> marks = row_marks(runs[i].sample);
       for (int32_t a = kv0; a < kv_end; a += B) {
         size_t first = i;
         while (runs[first].q_hi <= a) ++first;             // exists: the last run ends after a
         int64_t rows = 0;
         for (size_t r = first; r < j; ++r) rows += runs[r].q_hi - std::max(runs[r].q_lo, a);
-        ki.push_back(KvItem{a, std::min(B, kv_end - a), seg_base + (int32_t)first, seg_base + (int32_t)j, -1, 0, 0, 0});
+        ki.push_back(KvItem{a, std::min(B, kv_end - a), seg_base + (int32_t)first, seg_base + (int32_t)j, -1,
+                            marks.first, marks.second, 0});
         weight.push_back(rows);
       }
       i = j;
@@ -197,9 +203,27 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
       for (int z = 0; z < kNumTileSizes; ++z) { t->per_unit[pass].q_off[z].push_back(0); t->per_unit[pass].kv_off[z].push_back(0); }
       for (int ti = 0; ti < kNumSplitTiles; ++ti)
         for (int c = 0; c < kNumSplitClasses; ++c) { t->per_unit[pass].split_off[ti][c].push_back(0); t->per_unit[pass].reduce_off[ti][c].push_back(0); }
+      // reach[s]: (unit, end of the unit's last query row in sample s), in list order.  A unit collects into the
+      // key tiles of the sample that start before that end.
+      std::vector<std::vector<std::pair<int32_t, int32_t>>> reach(n);
+      for (int32_t u = 0; u < t->n_units[pass]; ++u)
+        for (int32_t i = t->unit_ptr[pass][u]; i < t->unit_ptr[pass][u + 1]; ++i) {
+          const slimattn_slice& x = slices[t->unit_slices[pass][i]];
+          auto& r = reach[x.sample];
+          if (!r.empty() && r.back().first == u) r.back().second = std::max(r.back().second, x.q_start + x.q_len);
+          else r.emplace_back(u, x.q_start + x.q_len);
+        }
       for (int32_t u = 0; u < t->n_units[pass]; ++u) {
         const int32_t a = t->unit_ptr[pass][u], b = t->unit_ptr[pass][u + 1];
-        append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a));
+        append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a),
+                     [&](int32_t sample) -> std::pair<int32_t, int32_t> {
+                       int32_t before = 0, after = 0;      // furthest reach of an earlier / a later unit (0: none)
+                       for (const auto& ur : reach[sample]) {
+                         if (ur.first < u) before = std::max(before, ur.second);
+                         if (ur.first > u) after = std::max(after, ur.second);
+                       }
+                       return {before, after};
+                     });
       }
     }
     std::vector<int32_t> all(n_slices);
@@ -207,7 +231,8 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     for (int z = 0; z < kNumTileSizes; ++z) { t->fused.q_off[z].push_back(0); t->fused.kv_off[z].push_back(0); }
     for (int ti = 0; ti < kNumSplitTiles; ++ti)
       for (int c = 0; c < kNumSplitClasses; ++c) { t->fused.split_off[ti][c].push_back(0); t->fused.reduce_off[ti][c].push_back(0); }
-    append_scope(t->fused, merge_runs(slices, all.data(), n_slices));
+    append_scope(t->fused, merge_runs(slices, all.data(), n_slices),
+                 [](int32_t) -> std::pair<int32_t, int32_t> { return {0, 0}; });
 
     // one blob, one upload
     std::vector<char> blob;
@@ -278,6 +303,30 @@ int64_t slimattn_tables_count(const slimattn_tables* t, int what) {
     case 5: case 6: case 7: case 8: return (int64_t)t->fused.reduce_items[0][what - 5].size();
     default: return -1;
   }
+}
+
+int slimattn_bwd_released_rows(const slimattn_tables* t, int32_t unit, int32_t* ranges, int32_t cap, int32_t* n_ranges) {
+  if (!t || !n_ranges || cap < 0 || (cap > 0 && !ranges)) return SLIMATTN_EINVAL;
+  if (unit < 0 || unit >= t->n_units[1]) return SLIMATTN_EINVAL;
+  // per sample: the rows between the furthest reach of a later unit and this unit's own reach
+  std::vector<int32_t> mine(t->n_samples, 0), later(t->n_samples, 0);
+  for (int32_t u = unit; u < t->n_units[1]; ++u)
+    for (int32_t i = t->unit_ptr[1][u]; i < t->unit_ptr[1][u + 1]; ++i) {
+      const slimattn_slice& x = t->slices[t->unit_slices[1][i]];
+      int32_t& r = (u == unit ? mine : later)[x.sample];
+      r = std::max(r, x.q_start + x.q_len);
+    }
+  std::vector<std::pair<int32_t, int32_t>> merged;
+  for (int32_t s = 0; s < t->n_samples; ++s) {
+    const int32_t a = std::max(later[s], t->cu[s]), b = mine[s];
+    if (b <= a) continue;
+    if (!merged.empty() && merged.back().second == a) merged.back().second = b;
+    else merged.emplace_back(a, b);
+  }
+  *n_ranges = (int32_t)merged.size();
+  if ((size_t)cap < merged.size()) return SLIMATTN_ECAP;
+  for (size_t i = 0; i < merged.size(); ++i) { ranges[2 * i] = merged[i].first; ranges[2 * i + 1] = merged[i].second; }
+  return SLIMATTN_OK;
 }
 
 size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t hq, int32_t hkv, int32_t d) {
