@@ -286,7 +286,10 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(const bf16* __restrict_
 // ---------------------------------------------------------------------------------------------
 // Sum of the partial tiles of a divided key tile, in slot order (fixed, so the result does not
 // depend on which block finished first), added to the fp32 accumulators or written as bf16.
-// One block per (tile, kv head); a thread owns four consecutive columns of a row.
+// grid = (tiles x kv heads, kReduceSplit): a block takes a 1/kReduceSplit share of the tile's elements
+// (the launches are small, and few blocks with long dependent loops would only wait on memory);
+// a thread owns four consecutive columns of a row.
+constexpr int kReduceSplit = 16;
 template <int D>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ parts, float* __restrict__ acc_dk,
                                                            float* __restrict__ acc_dv, bf16* __restrict__ dK,
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restri
   const KvReduce it = items[blockIdx.x / Hkv];
   const int hk = blockIdx.x % Hkv;
   const int kTile = tile_rows * D;                     // elements of one partial dK (or dV) tile
-  for (int e = threadIdx.x * 4; e < 2 * kTile; e += 256 * 4) {
+  for (int e = (blockIdx.y * 256 + threadIdx.x) * 4; e < 2 * kTile; e += kReduceSplit * 256 * 4) {
     const int which = e / kTile, r = (e % kTile) / D, c = e % D;
     if (r >= it.kv_rows) continue;
     floatx4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -366,7 +369,7 @@ int launch_bwd_reduce_bf16(const LaunchCtx& c, const float* parts, float* acc_dk
                            const KvReduce* items, int n_items, int tile_rows) {
   if (n_items == 0) return 0;
   const slimattn_params& p = *c.p;
-  const dim3 grid((unsigned)(n_items * p.n_kv_heads)), block(256);
+  const dim3 grid((unsigned)(n_items * p.n_kv_heads), kReduceSplit), block(256);
   if (p.head_dim == 128)
     hipLaunchKernelGGL(reduce_parts_kernel<128>, grid, block, 0, (hipStream_t)c.stream, parts, acc_dk, acc_dv, (bf16*)dK,
                        (bf16*)dV, items, p.n_kv_heads, tile_rows);

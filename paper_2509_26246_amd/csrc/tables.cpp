@@ -46,7 +46,7 @@ std::vector<Run> merge_runs(const slimattn_slice* sl, const int32_t* ids, int32_
 // than kMinPartRows).  A part is an item of
 // its own, with its own (cut) runs appended to segs and a partial-tile slot; slots of one tile are
 // consecutive and the reduction adds them in that order, so results do not depend on scheduling.
-constexpr int64_t kMinPartRows = 1024;
+constexpr int64_t kMinPartRows = 256;
 
 void append_split(ScopeLists& L, int ti, const std::vector<KvItem>& ki, const std::vector<int64_t>& weight) {
   const int64_t kBlockSlots = kSplitBlockSlots[ti];
