@@ -140,6 +140,9 @@ def main():
     ap.add_argument("--per-unit", action="store_true", help="main measurement: one launch per unit instead of one fused launch")
     ap.add_argument("--seeds", default="", help="comma-separated subset of the workload's seeds (default: all four)")
     ap.add_argument("--brief", action="store_true", help="skip the per-seed and the secondary per-unit measurements")
+    ap.add_argument("--partition", choices=["policy", "solver"], default="policy",
+                    help="slice table and unit lists of the main measurement: the workload's greedy policies on fixed-size "
+                         "slices, or the exact min-max partition solver (same unit counts, cuts on 256-row granules)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -158,22 +161,38 @@ def main():
     seeds = [int(x) for x in args.seeds.split(",")] if args.seeds else list(W.SEEDS)
     packs = [_pack(w, seed) for seed in seeds]
     d, hq, hkv = w.head_dim, w.n_q_heads, w.n_kv_heads
-    probs, pairs, tabs, build_ms = [], [], [], {"slices_and_units": [], "derive_and_upload": []}
-    for L, q, k, v, dO in packs:
-        t0 = time.perf_counter()
+    def policy_tables(L):
         cu, sl = S.build_slices(L, w.slice_size)
-        fu = S.build_units(cu, sl, w.fwd_policy[0], **w.fwd_policy[1])
-        bu = S.build_units(cu, sl, w.bwd_policy[0], **w.bwd_policy[1])
-        t1 = time.perf_counter()
-        torch.cuda.set_device(0)
-        tmp = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1])      # timed on its own: derived work-lists + one upload
-        t2 = time.perf_counter()
-        tmp.destroy()
-        build_ms["slices_and_units"].append((t1 - t0) * 1e3)
-        build_ms["derive_and_upload"].append((t2 - t1) * 1e3)
-        probs.append(H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=(w.dtype == "bf16")))
-        pairs.append(int(sum(S.slice_pairs(r) for r in sl)))
-        tabs.append((cu, sl, fu, bu))
+        return cu, sl, S.build_units(cu, sl, w.fwd_policy[0], **w.fwd_policy[1]), S.build_units(cu, sl, w.bwd_policy[0], **w.bwd_policy[1])
+
+    def solver_tables(L):
+        """The exact partition for the same numbers of units the policies produce and the same cost weights; slices no
+        longer than the workload's slice size."""
+        _, _, fu, bu = policy_tables(L)
+        wq_f, wl_f = w.fwd_policy[1].get("w_quad", 2), w.fwd_policy[1].get("w_lin", 0)
+        wq_b, wl_b = w.bwd_policy[1].get("w_quad", 5), w.bwd_policy[1].get("w_lin", 0)
+        r = S.solve_partition(L, m_fwd=len(fu[0]) - 1, m_bwd=len(bu[0]) - 1, w_quad_fwd=wq_f, w_lin_fwd=wl_f, w_quad_bwd=wq_b,
+                              w_lin_bwd=wl_b, granule=256, max_slice=w.slice_size)
+        return r["cu"], r["slices"], r["fwd"], r["bwd"]
+
+    def make_problems(table_fn):
+        probs, pairs, tabs, build_ms = [], [], [], {"slices_and_units": [], "derive_and_upload": []}
+        for L, q, k, v, dO in packs:
+            t0 = time.perf_counter()
+            cu, sl, fu, bu = table_fn(L)
+            t1 = time.perf_counter()
+            torch.cuda.set_device(0)
+            tmp = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1])      # timed on its own: derived work-lists + one upload
+            t2 = time.perf_counter()
+            tmp.destroy()
+            build_ms["slices_and_units"].append((t1 - t0) * 1e3)
+            build_ms["derive_and_upload"].append((t2 - t1) * 1e3)
+            probs.append(H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=(w.dtype == "bf16")))
+            pairs.append(int(sum(S.slice_pairs(r) for r in sl)))
+            tabs.append((cu, sl, fu, bu))
+        return probs, pairs, tabs, build_ms
+
+    probs, pairs, tabs, build_ms = make_problems(solver_tables if args.partition == "solver" else policy_tables)
     n_packs = len(probs)
 
     # A plain device copy of known size (256 MiB read + 256 MiB written) before anything else: under
@@ -309,7 +328,7 @@ def main():
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "total_tokens": w.total_tokens if w.total_tokens > 0 else int(T_mean),
                    "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d, "slice_size": w.slice_size, "seeds": seeds,
-                   "launch": mode, "fwd_policy": w.fwd_policy[0], "bwd_policy": w.bwd_policy[0],
+                   "launch": mode, "partition": args.partition, "fwd_policy": w.fwd_policy[0], "bwd_policy": w.bwd_policy[0],
                    "fwd_units": [p.tables.n_fwd_units for p in probs], "bwd_units": [p.tables.n_bwd_units for p in probs]},
         "fwd_tflops": main_sum["fwd_tflops"], "bwd_tflops": main_sum["bwd_tflops"],
         "fwd_pct_bf16_peak": main_sum["fwd_pct_bf16_peak"], "bwd_pct_bf16_peak": main_sum["bwd_pct_bf16_peak"],
@@ -336,6 +355,23 @@ def main():
             s_, _ = summarise(wl, pr, rc, args.steps)
             s_["unit_ms"] = unit_spread(rc, args.steps)
             out["per_unit"] = s_
+            if args.partition == "policy":
+                # the same packs partitioned by the exact solver instead of the greedy policies (same unit counts):
+                # what it does to the spread of per-unit times
+                for p_ in probs:
+                    p_.tables.destroy()
+                keep = (probs, pairs, tabs)
+                del probs[:]
+                probs2, pairs2, tabs2, bms2 = make_problems(solver_tables)
+                probs.extend(probs2); pairs[:] = pairs2; tabs[:] = tabs2
+                wl, pr, rc = measure(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
+                s2, _ = summarise(wl, pr, rc, args.steps)
+                s2["unit_ms"] = unit_spread(rc, args.steps)
+                s2["fwd_units"] = [p_.tables.n_fwd_units for p_ in probs]
+                s2["bwd_units"] = [p_.tables.n_bwd_units for p_ in probs]
+                s2["slices"] = [len(t_[1]) for t_ in tabs]
+                s2["solve_ms"] = statistics.median(bms2["slices_and_units"])
+                out["per_unit_solver"] = s2
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(w, packs, seeds[0])
     print(json.dumps(out))

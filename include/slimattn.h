@@ -40,6 +40,7 @@ extern "C" {
 #define SLIMATTN_ECAP    -3   /* an output array is too small */
 #define SLIMATTN_EHIP    -4   /* a HIP call failed; code via slimattn_last_hip_error() */
 #define SLIMATTN_ENOMEM  -5   /* host allocation failed */
+#define SLIMATTN_EINFEASIBLE -7 /* slimattn_solve_partition: the token cap alone needs more units than allowed */
 #define SLIMATTN_ESCRATCH -6  /* slimattn_bwd_static: the pack needs more scratch than the built-in array holds */
 
 #define SLIMATTN_F32   0      /* q,k,v,o,dO,dQ,dK,dV are float; all arithmetic fp32 */
@@ -122,6 +123,44 @@ int slimattn_build_slices_from_bounds(const int32_t* lengths, int32_t n, const i
 int slimattn_build_units(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
                          const slimattn_policy* policy, int32_t* unit_ptr, int32_t* unit_slices,
                          int32_t cap_units, int32_t* n_units);
+
+/* ---- partition solver (host only) ---------------------------------------------------------------- */
+
+/* Parameters of slimattn_solve_partition.  A row that sees i + 1 keys costs w_quad * (i + 1) + w_lin in its
+ * pass (the paper gives only the ratios: attention backward = 2.5 x forward, linear layers 2 x; e.g. forward
+ * 2 / lambda, backward 5 / 2 lambda in units of 2*d*Hq flops). */
+typedef struct slimattn_solver {
+  int32_t m_fwd, m_bwd;                  /* at most this many forward / backward units */
+  int64_t w_quad_fwd, w_lin_fwd;         /* forward cost weights  (0 .. 2^20, 0 .. 2^30) */
+  int64_t w_quad_bwd, w_lin_bwd;         /* backward cost weights */
+  int32_t granule;                       /* cuts fall on multiples of this many rows from a sample's start (>= 1) */
+  int32_t token_cap_fwd, token_cap_bwd;  /* at most this many query rows per unit (0: no cap); a single granule may exceed it */
+  int32_t max_slice;                     /* extra cuts every max_slice rows so that no slice is longer (0: none) */
+} slimattn_solver;
+
+/* Exact solution of the paper's Phase 2 problem in the form this library states it (Balanced Packing &
+ * Asymmetric Partitioning Solver: per-unit target tau = W / m, long samples cut into slices over several units,
+ * short ones packed, slice boundaries decided by the optimisation; Asymmetric Partition: a partition of its own
+ * for the backward pass, same unit order).  Units are contiguous pieces of the walk (samples by descending
+ * length, ties by index; rows upwards forward, downwards backward); the largest unit cost is minimised over all
+ * cuts on granule boundaries, for each pass separately (bottlenecks[0] forward, [1] backward receive the optimum;
+ * optional); the cuts returned close a unit only when the next granule would exceed that optimum or the token
+ * cap.  The slice table (same record layout and order as slimattn_build_slices) is the union of both passes'
+ * cuts; both unit lists are CSR over it and satisfy SLIMATTN_CHECK_ORDER.
+ * All arrays HOST: lengths [n]; cu_out [n+1]; slices [cap_slices]; *_unit_ptr [cap_units+1]; *_unit_slices
+ * [cap_slices].  ECAP if a capacity is too small (n_slices, n_fwd_units, n_bwd_units are still set);
+ * EINFEASIBLE if the token cap needs more than m units; EINVAL on bad parameters. */
+int slimattn_solve_partition(const int32_t* lengths, int32_t n, const slimattn_solver* sp, int32_t* cu_out,
+                             slimattn_slice* slices, int32_t cap_slices, int32_t* n_slices, int32_t* fwd_unit_ptr,
+                             int32_t* fwd_unit_slices, int32_t* n_fwd_units, int32_t* bwd_unit_ptr,
+                             int32_t* bwd_unit_slices, int32_t* n_bwd_units, int32_t cap_units, int64_t* bottlenecks);
+
+/* The optimum of the same problem for several candidate unit counts (the paper evaluates several MicroPack
+ * counts m and keeps the best; Primitive Measurements and Search Space), computed by n_threads workers:
+ * fwd_bottleneck[i], bwd_bottleneck[i] for m_list[i] (used for both passes; m_fwd / m_bwd of `sp` are
+ * ignored); -1 where the token cap makes m_list[i] units infeasible.  All arrays HOST [n_m]. */
+int slimattn_solve_bottlenecks(const int32_t* lengths, int32_t n, const slimattn_solver* sp, const int32_t* m_list,
+                               int32_t n_m, int32_t n_threads, int64_t* fwd_bottleneck, int64_t* bwd_bottleneck);
 
 /* Checks tables against the rules of the paper's PackFlow Pipeline Parallelism Scheduling section (slice order
  * within a sample preserved in the forward pass, backward first-in last-out) and of the MicroPack definition

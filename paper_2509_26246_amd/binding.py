@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -35,6 +35,12 @@ class _Policy(C.Structure):
     _fields_ = [("kind", C.c_int32), ("m", C.c_int32), ("w_quad", C.c_int64), ("w_lin", C.c_int64),
                 ("backward", C.c_int32), ("descending", C.c_int32), ("cap", C.c_int32), ("m_min", C.c_int32),
                 ("theta_num", C.c_int32), ("theta_den", C.c_int32)]
+
+
+class _Solver(C.Structure):
+    _fields_ = [("m_fwd", C.c_int32), ("m_bwd", C.c_int32), ("w_quad_fwd", C.c_int64), ("w_lin_fwd", C.c_int64),
+                ("w_quad_bwd", C.c_int64), ("w_lin_bwd", C.c_int64), ("granule", C.c_int32), ("token_cap_fwd", C.c_int32),
+                ("token_cap_bwd", C.c_int32), ("max_slice", C.c_int32)]
 
 
 class _Params(C.Structure):
@@ -59,6 +65,10 @@ def load_library():
     lib.slimattn_build_slices_from_bounds.argtypes = [i32p, C.c_int32, i32p, i32p, i32p, vp, C.c_int32, i32p]
     lib.slimattn_build_units.argtypes = [i32p, C.c_int32, vp, C.c_int32, C.POINTER(_Policy), i32p, i32p, C.c_int32, i32p]
     lib.slimattn_validate.argtypes = [i32p, C.c_int32, vp, C.c_int32, i32p, i32p, C.c_int32, C.c_int, C.POINTER(C.c_char_p)]
+    i64p = C.POINTER(C.c_int64)
+    lib.slimattn_solve_partition.argtypes = [i32p, C.c_int32, C.POINTER(_Solver), i32p, vp, C.c_int32, i32p, i32p, i32p, i32p,
+                                             i32p, i32p, i32p, C.c_int32, i64p]
+    lib.slimattn_solve_bottlenecks.argtypes = [i32p, C.c_int32, C.POINTER(_Solver), i32p, C.c_int32, C.c_int32, i64p, i64p]
     lib.slimattn_slice_pairs.argtypes = [vp]
     lib.slimattn_slice_pairs.restype = C.c_int64
     for f in (lib.slimattn_flops_fwd, lib.slimattn_flops_bwd):
@@ -150,6 +160,52 @@ def build_units(cu, slices, policy: str, **p) -> Tuple[np.ndarray, np.ndarray]:
     if rc != 0:
         raise SlimAttnError(rc, "slimattn_build_units")
     return ptr[:nu.value + 1].copy(), flat[:ns].copy()
+
+
+def _solver(m_fwd=1, m_bwd=1, w_quad_fwd=2, w_lin_fwd=0, w_quad_bwd=5, w_lin_bwd=0, granule=1, token_cap_fwd=0,
+            token_cap_bwd=0, max_slice=0) -> _Solver:
+    return _Solver(m_fwd=m_fwd, m_bwd=m_bwd, w_quad_fwd=w_quad_fwd, w_lin_fwd=w_lin_fwd, w_quad_bwd=w_quad_bwd,
+                   w_lin_bwd=w_lin_bwd, granule=granule, token_cap_fwd=token_cap_fwd, token_cap_bwd=token_cap_bwd,
+                   max_slice=max_slice)
+
+
+def solve_partition(lengths: Sequence[int], **params):
+    """slimattn_solve_partition -> dict(cu, slices, fwd=(unit_ptr, unit_slices), bwd=(...), bottleneck_fwd, bottleneck_bwd)."""
+    lib = load_library()
+    L = _i32(lengths)
+    sp = _solver(**params)
+    cu = np.zeros(len(L) + 1, np.int32)
+    ns, nf, nb = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    bott = (C.c_int64 * 2)()
+    one = np.zeros(1, np.int32)
+    rc = lib.slimattn_solve_partition(_p(L), len(L), C.byref(sp), _p(cu), None, 0, C.byref(ns), _p(one), None, C.byref(nf),
+                                      _p(one), None, C.byref(nb), 0, bott)
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_solve_partition")
+    cap_s, cap_u = max(ns.value, 1), max(nf.value, nb.value, 1)
+    sl = np.zeros((cap_s, 8), np.int32)
+    fp, bp = np.zeros(cap_u + 1, np.int32), np.zeros(cap_u + 1, np.int32)
+    fs, bs = np.zeros(cap_s, np.int32), np.zeros(cap_s, np.int32)
+    rc = lib.slimattn_solve_partition(_p(L), len(L), C.byref(sp), _p(cu), sl.ctypes.data, cap_s, C.byref(ns), _p(fp), _p(fs),
+                                      C.byref(nf), _p(bp), _p(bs), C.byref(nb), cap_u, bott)
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_solve_partition")
+    n = ns.value
+    return {"cu": cu, "slices": sl[:n].copy(), "fwd": (fp[:nf.value + 1].copy(), fs[:n].copy()),
+            "bwd": (bp[:nb.value + 1].copy(), bs[:n].copy()), "bottleneck_fwd": int(bott[0]), "bottleneck_bwd": int(bott[1])}
+
+
+def solve_bottlenecks(lengths: Sequence[int], m_list: Sequence[int], n_threads: int = 4, **params):
+    """slimattn_solve_bottlenecks -> (forward optima, backward optima) for the candidate unit counts."""
+    lib = load_library()
+    L, M = _i32(lengths), _i32(m_list)
+    sp = _solver(**params)
+    f, b = np.zeros(len(M), np.int64), np.zeros(len(M), np.int64)
+    i64 = lambda a: a.ctypes.data_as(C.POINTER(C.c_int64))
+    rc = lib.slimattn_solve_bottlenecks(_p(L), len(L), C.byref(sp), _p(M), len(M), n_threads, i64(f), i64(b))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_solve_bottlenecks")
+    return f, b
 
 
 def validate(cu, slices, unit_ptr, unit_slices, mode: int = CHECK_FORWARD) -> Tuple[int, str]:

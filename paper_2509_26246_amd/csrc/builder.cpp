@@ -301,6 +301,7 @@ const char* slimattn_strerror(int code) {
     case SLIMATTN_ECAP: return "output capacity too small";
     case SLIMATTN_EHIP: return "HIP call failed";
     case SLIMATTN_ENOMEM: return "out of host memory";
+    case SLIMATTN_EINFEASIBLE: return "the token cap needs more units than allowed";
     case SLIMATTN_ESCRATCH: return "workspace need exceeds the built-in scratch array";
     default: return "unknown error";
   }

@@ -150,3 +150,79 @@ def test_error_codes():
     assert lib.slimattn_build_slices(p(L), 2, 4, p(cu), None, 0, ctypes.byref(n)) == -3 and n.value == 5
     with pytest.raises(S.SlimAttnError):
         S.build_units(cu, np.zeros((1, 8), np.int32), "PREFIX_FILL", m=0, w_quad=1)
+
+
+# ---- partition solver (slimattn_solve_partition) against the partition oracle -----------------------------------
+
+def _native_vs_oracle_partition(lengths, mf, mb, wqf, wlf, wqb, wlb, **kw):
+    from oracle import solver as SV
+    want = SV.solve_partition(lengths, mf, mb, wqf, wlf, wqb, wlb, **kw)      # ValueError when no partition exists
+    got = S.solve_partition(lengths, m_fwd=mf, m_bwd=mb, w_quad_fwd=wqf, w_lin_fwd=wlf, w_quad_bwd=wqb, w_lin_bwd=wlb, **kw)
+    assert got["bottleneck_fwd"] == want["bottleneck_fwd"] and got["bottleneck_bwd"] == want["bottleneck_bwd"], (lengths, mf, mb, kw)
+    assert np.array_equal(got["cu"], want["cu"]) and np.array_equal(got["slices"], want["slices"]), (lengths, mf, mb, kw)
+    for key in ("fwd", "bwd"):
+        assert np.array_equal(got[key][0], want[key][0]) and np.array_equal(got[key][1], want[key][1]), (key, lengths, mf, mb, kw)
+    return got
+
+
+def test_native_solver_golden_and_bit_exact_vs_oracle():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "solver_tiny.json")))
+    p = g["partition"]
+    got = S.solve_partition(g["lengths"], m_fwd=p["m_fwd"], m_bwd=p["m_bwd"], w_quad_fwd=2, w_quad_bwd=5, granule=1)
+    assert got["slices"].tolist() == p["slices"] and (got["bottleneck_fwd"], got["bottleneck_bwd"]) == (22, 55)
+    for key, want in (("fwd", p["fwd_units"]), ("bwd", p["bwd_units"])):
+        up, us = got[key]
+        assert [us[up[u]:up[u + 1]].tolist() for u in range(len(up) - 1)] == want
+    for case in g["cases"]:                       # each pass's optimum, through the candidate routine
+        kw = {"w_quad_fwd": case["w_quad"], "w_lin_fwd": case["w_lin"], "w_quad_bwd": case["w_quad"], "w_lin_bwd": case["w_lin"],
+              "token_cap_fwd": case["token_cap"], "token_cap_bwd": case["token_cap"]}
+        f, b = S.solve_bottlenecks(g["lengths"], [case["m"]], **kw)
+        assert (b if case["pass"] == "backward" else f)[0] == case["bottleneck"]
+    r = np.random.default_rng(19)
+    for _ in range(40):
+        lengths = r.integers(0, 70, size=r.integers(1, 8)).tolist()
+        if sum(lengths) == 0:
+            continue
+        kw = {"granule": int(r.integers(1, 9)), "max_slice": int(r.choice([0, 0, 16, 40]))}
+        if r.random() < 0.4:
+            kw["token_cap_fwd"] = int(r.integers(20, 90)); kw["token_cap_bwd"] = int(r.integers(20, 90))
+        mf, mb = int(r.integers(1, 8)), int(r.integers(1, 10))
+        try:
+            got = _native_vs_oracle_partition(lengths, mf, mb, 2, int(r.integers(0, 4)), 5, int(r.integers(0, 7)), **kw)
+        except ValueError:                        # the oracle found no partition under the cap: so must the library
+            with pytest.raises(S.SlimAttnError) as e:
+                S.solve_partition(lengths, m_fwd=mf, m_bwd=mb, w_quad_fwd=2, w_quad_bwd=5, **kw)
+            assert e.value.code == -7
+            continue
+        for key, mode in (("fwd", S.CHECK_FORWARD), ("bwd", S.CHECK_BACKWARD)):
+            assert S.validate(got["cu"], got["slices"], *got[key], mode | S.CHECK_ORDER) == (0, "")
+
+
+def test_native_solver_candidates_and_full_size():
+    from oracle import tables as T
+    w = W.WORKLOADS["cfg3_extreme_skew"]
+    L = W.draw_lengths(w, np.random.default_rng(1))
+    lam = 53248                                   # linear work per token of a Llama-3-8B-shaped layer, in units of 2*d*Hq flops
+    kw = dict(w_quad_fwd=2, w_lin_fwd=lam, w_quad_bwd=5, w_lin_bwd=2 * lam, granule=256)
+    ms = [8, 16, 32, 64, 128]
+    f, b = S.solve_bottlenecks(L, ms, n_threads=4, **kw)
+    f1, b1 = S.solve_bottlenecks(L, ms, n_threads=1, **kw)
+    assert np.array_equal(f, f1) and np.array_equal(b, b1)
+    assert all(f[i] >= f[i + 1] for i in range(len(ms) - 1)) and all(b[i] >= b[i + 1] for i in range(len(ms) - 1))
+    for i, m in enumerate(ms):
+        got = S.solve_partition(L, m_fwd=m, m_bwd=m, **kw)
+        assert (got["bottleneck_fwd"], got["bottleneck_bwd"]) == (int(f[i]), int(b[i]))
+        for key, wq, wl, B in (("fwd", 2, lam, f[i]), ("bwd", 5, 2 * lam, b[i])):
+            costs = T.unit_costs(got["slices"], *got[key], wq, wl)
+            W_ = sum(costs)
+            gmax = 256 * (wq * int(L.max()) + wl)                      # no granule costs more than its rows at the last row's price
+            assert len(costs) <= m and max(costs) == B and -(-W_ // m) <= B <= W_ // m + gmax
+        assert S.validate(got["cu"], got["slices"], *got["bwd"], S.CHECK_BACKWARD | S.CHECK_ORDER) == (0, "")
+    # every error path returns a code
+    with pytest.raises(S.SlimAttnError):
+        S.solve_partition([5, 5], m_fwd=0, m_bwd=1)
+    with pytest.raises(S.SlimAttnError):
+        S.solve_partition([5, -1], m_fwd=1, m_bwd=1)
+    with pytest.raises(S.SlimAttnError) as e:
+        S.solve_partition([100], m_fwd=2, m_bwd=2, token_cap_fwd=10, granule=5)
+    assert e.value.code == -7
