@@ -239,6 +239,38 @@ def main():
         out["bwd_pct_bf16_peak"] = 100 * out["bwd_tflops"] / BF16_MFMA_PEAK_TFLOPS
         return out, per
 
+    def unit_times(rec):
+        """{(pass, pack, unit): mean ms over the steps in which that pack ran} from per-launch records."""
+        cls, ps, un, ms = rec
+        step, prev_pass, acc = 0, 0, {}
+        for p_, u, m in zip(ps, un, ms):                # launches come in step order: forward, then backward
+            if p_ == 0 and prev_pass == 1:
+                step += 1
+            prev_pass = p_
+            if u >= 0:
+                key = (int(p_), step % n_packs, int(u))
+                tot, cnt = acc.get(key, (0.0, set()))
+                cnt.add(step)
+                acc[key] = (tot + float(m), cnt)
+        return {k_: tot / len(cnt) for k_, (tot, cnt) in acc.items()}
+
+    def pipeline_sim(rec):
+        """The measured per-unit times through the DAG simulator: makespan and idle share of a 1F1B pipeline whose
+        every stage holds one such attention layer, per number of stages (mean over the packs)."""
+        ut = unit_times(rec)
+        out = {}
+        for stages in (1, 2, 4, 8):
+            tot, busy = 0.0, 0.0
+            for i, (cu, sl, fu, bu) in enumerate(tabs):
+                fc = [int(round(ut[(0, i, u)] * 1e6)) for u in range(len(fu[0]) - 1)]      # ns
+                bc = [int(round(ut[(1, i, u)] * 1e6)) for u in range(len(bu[0]) - 1)]
+                g = S.dag_build_1f1b(sl, fu, bu, stages, fc, bc)
+                _, _, t_total = S.dag_timeline(g["weight"], g["edge_from"], g["edge_to"])
+                tot += t_total * 1e-6
+                busy += (sum(fc) + sum(bc)) * 1e-6
+            out[str(stages)] = {"makespan_ms": tot / n_packs, "idle_share": 1.0 - busy / tot if tot > 0 else 0.0}
+        return out
+
     def unit_spread(rec, steps):
         """Time of each scheduling unit (all kernels launched for it), averaged over the steps in which the same
         pack ran; spread over the units of all packs.  Only launches tied to a unit count."""
@@ -338,6 +370,7 @@ def main():
     }
     if args.per_unit:
         out["unit_ms"] = unit_spread(rec, args.steps)
+        out["pipeline_1f1b"] = pipeline_sim(rec)
 
     if not args.brief:
         # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
@@ -354,6 +387,7 @@ def main():
             wl, pr, rc = measure(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
             s_, _ = summarise(wl, pr, rc, args.steps)
             s_["unit_ms"] = unit_spread(rc, args.steps)
+            s_["pipeline_1f1b"] = pipeline_sim(rc)
             out["per_unit"] = s_
             if args.partition == "policy":
                 # the same packs partitioned by the exact solver instead of the greedy policies (same unit counts):
@@ -367,6 +401,7 @@ def main():
                 wl, pr, rc = measure(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
                 s2, _ = summarise(wl, pr, rc, args.steps)
                 s2["unit_ms"] = unit_spread(rc, args.steps)
+                s2["pipeline_1f1b"] = pipeline_sim(rc)
                 s2["fwd_units"] = [p_.tables.n_fwd_units for p_ in probs]
                 s2["bwd_units"] = [p_.tables.n_bwd_units for p_ in probs]
                 s2["slices"] = [len(t_[1]) for t_ in tabs]

@@ -162,6 +162,39 @@ int slimattn_solve_partition(const int32_t* lengths, int32_t n, const slimattn_s
 int slimattn_solve_bottlenecks(const int32_t* lengths, int32_t n, const slimattn_solver* sp, const int32_t* m_list,
                                int32_t n_m, int32_t n_threads, int64_t* fwd_bottleneck, int64_t* bwd_bottleneck);
 
+/* ---- DAG-based pipeline simulator (host only) -------------------------------------------------------- */
+
+#define SLIMATTN_ACTION_FWD     0
+#define SLIMATTN_ACTION_BWD     1
+#define SLIMATTN_EDGE_STAGE     0   /* inter-stage data dependency */
+#define SLIMATTN_EDGE_SLICE     1   /* inter-slice data dependency (KV cache forward, KV gradients backward) */
+#define SLIMATTN_EDGE_SCHEDULE  2   /* order of tasks on one stage */
+
+/* Execution timeline on a task graph (paper: DAG resolution; Execution timeline calculation on the DAG):
+ * Start(v) = max(0, Finish(u) over edges (u, v)), Finish(v) = Start(v) + weight[v], *total = max Finish, by
+ * topological order and edge relaxation, O(V + E).  weight [n_vertices] >= 0 in any integer time unit; edges
+ * as (edge_from[e], edge_to[e]) vertex indices; start, finish [n_vertices] out.  All arrays HOST.
+ * ETABLE if the graph has a cycle (the schedule would deadlock); EINVAL on bad indices or negative weights. */
+int slimattn_dag_timeline(int32_t n_vertices, const int64_t* weight, int32_t n_edges, const int32_t* edge_from,
+                          const int32_t* edge_to, int64_t* start, int64_t* finish, int64_t* total);
+
+/* Task graph of a 1F1B pipeline of n_stages stages over the given slice table and forward / backward unit lists
+ * (paper: DAG-based pipeline representation -- vertices (stage, action, data unit), inter-stage, inter-slice and
+ * schedule dependencies; PackFlow Pipeline Parallelism Scheduling -- units first-in first-out, a sample's
+ * backward after all of its slices' forward, an extra forward unit while the next backward unit is not ready).
+ * Vertex ids: forward task of unit u on stage s = s * n_fwd + u; backward task of unit v on stage s =
+ * n_stages * n_fwd + s * n_bwd + v.  vertex [3 * cap_vertices] receives (stage, action, unit) per vertex, weight
+ * [cap_vertices] the task times taken from fwd_cost [n_fwd] / bwd_cost [n_bwd] (the same on every stage);
+ * edge_from, edge_to, edge_kind [cap_edges] the edges with their SLIMATTN_EDGE_* kind.  With asymmetric unit
+ * lists a backward unit at the last stage depends on every forward unit it shares a slice with.  All arrays
+ * HOST.  ECAP if a capacity is too small (n_vertices, n_edges are still set); ETABLE on inconsistent lists. */
+int slimattn_dag_build_1f1b(const slimattn_slice* slices, int32_t n_slices, const int32_t* fwd_unit_ptr,
+                            const int32_t* fwd_unit_slices, int32_t n_fwd, const int32_t* bwd_unit_ptr,
+                            const int32_t* bwd_unit_slices, int32_t n_bwd, int32_t n_stages, const int64_t* fwd_cost,
+                            const int64_t* bwd_cost, int32_t* vertex, int64_t* weight, int32_t cap_vertices,
+                            int32_t* n_vertices, int32_t* edge_from, int32_t* edge_to, int32_t* edge_kind,
+                            int32_t cap_edges, int32_t* n_edges);
+
 /* Checks tables against the rules of the paper's PackFlow Pipeline Parallelism Scheduling section (slice order
  * within a sample preserved in the forward pass, backward first-in last-out) and of the MicroPack definition
  * (SlimPack System).  Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear

@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -69,6 +69,9 @@ def load_library():
     lib.slimattn_solve_partition.argtypes = [i32p, C.c_int32, C.POINTER(_Solver), i32p, vp, C.c_int32, i32p, i32p, i32p, i32p,
                                              i32p, i32p, i32p, C.c_int32, i64p]
     lib.slimattn_solve_bottlenecks.argtypes = [i32p, C.c_int32, C.POINTER(_Solver), i32p, C.c_int32, C.c_int32, i64p, i64p]
+    lib.slimattn_dag_timeline.argtypes = [C.c_int32, i64p, C.c_int32, i32p, i32p, i64p, i64p, i64p]
+    lib.slimattn_dag_build_1f1b.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i64p, i64p,
+                                            i32p, i64p, C.c_int32, i32p, i32p, i32p, i32p, C.c_int32, i32p]
     lib.slimattn_slice_pairs.argtypes = [vp]
     lib.slimattn_slice_pairs.restype = C.c_int64
     for f in (lib.slimattn_flops_fwd, lib.slimattn_flops_bwd):
@@ -206,6 +209,48 @@ def solve_bottlenecks(lengths: Sequence[int], m_list: Sequence[int], n_threads: 
     if rc != 0:
         raise SlimAttnError(rc, "slimattn_solve_bottlenecks")
     return f, b
+
+
+def _i64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _p64(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def dag_timeline(weight, edge_from, edge_to):
+    """slimattn_dag_timeline -> (start, finish, total)."""
+    lib = load_library()
+    w, ef, et = _i64(weight), _i32(edge_from), _i32(edge_to)
+    start, finish = np.zeros(len(w), np.int64), np.zeros(len(w), np.int64)
+    total = C.c_int64(0)
+    rc = lib.slimattn_dag_timeline(len(w), _p64(w), len(ef), _p(ef), _p(et), _p64(start), _p64(finish), C.byref(total))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_dag_timeline")
+    return start, finish, int(total.value)
+
+
+def dag_build_1f1b(slices, fwd_units, bwd_units, n_stages: int, fwd_cost, bwd_cost):
+    """slimattn_dag_build_1f1b -> dict(vertex [n,3], weight [n], edge_from, edge_to, edge_kind)."""
+    lib = load_library()
+    sl = _i32(slices).reshape(-1, 8)
+    fp, fs, bp, bs = _i32(fwd_units[0]), _i32(fwd_units[1]), _i32(bwd_units[0]), _i32(bwd_units[1])
+    fc, bc = _i64(fwd_cost), _i64(bwd_cost)
+    nv, ne = C.c_int32(0), C.c_int32(0)
+    args = (sl.ctypes.data, len(sl), _p(fp), _p(fs), len(fp) - 1, _p(bp), _p(bs), len(bp) - 1, n_stages, _p64(fc), _p64(bc))
+    rc = lib.slimattn_dag_build_1f1b(*args, None, None, 0, C.byref(nv), None, None, None, 0, C.byref(ne))
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_dag_build_1f1b")
+    vertex, weight = np.zeros((max(nv.value, 1), 3), np.int32), np.zeros(max(nv.value, 1), np.int64)
+    ef, et, ek = (np.zeros(max(ne.value, 1), np.int32) for _ in range(3))
+    rc = lib.slimattn_dag_build_1f1b(*args, _p(vertex), _p64(weight), nv.value, C.byref(nv), _p(ef), _p(et), _p(ek), ne.value,
+                                     C.byref(ne))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_dag_build_1f1b")
+    n, m = nv.value, ne.value
+    return {"vertex": vertex[:n].copy(), "weight": weight[:n].copy(), "edge_from": ef[:m].copy(), "edge_to": et[:m].copy(),
+            "edge_kind": ek[:m].copy()}
 
 
 def validate(cu, slices, unit_ptr, unit_slices, mode: int = CHECK_FORWARD) -> Tuple[int, str]:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslimattn.so")
-SOURCES = ["builder.cpp", "solver.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "fwd_wide_bf16.hip", "bwd_bf16.hip", "dkdv_wide_bf16.hip"]
+SOURCES = ["builder.cpp", "solver.cpp", "dag.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "fwd_wide_bf16.hip", "bwd_bf16.hip", "dkdv_wide_bf16.hip"]
 # dkdv_wide_bf16.hip keeps its dK/dV accumulators in the accumulation registers through inline asm; the
 # builtin products of the same kernel must then be told to stay in architectural registers.
 EXTRA_FLAGS = {"dkdv_wide_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
@@ -37,7 +37,7 @@ def _compile(src: str, objdir: str) -> str:
 def build(verbose: bool = False) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(9, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(lambda s: _compile(s, objdir), SOURCES))
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)
