@@ -126,7 +126,7 @@ def _spread(xs):
         return None
     mean = sum(xs) / len(xs)
     sd = (sum((x - mean) ** 2 for x in xs) / len(xs)) ** 0.5
-    return {"n_units": len(xs), "min_ms": min(xs), "median_ms": statistics.median(xs), "max_ms": max(xs),
+    return {"n_units": len(xs), "min_ms": min(xs), "median_ms": statistics.median(xs), "max_ms": max(xs), "mean_ms": mean,
             "cv": sd / mean if mean > 0 else 0.0}
 
 
@@ -272,24 +272,20 @@ def main():
         return out
 
     def unit_spread(rec, steps):
-        """Time of each scheduling unit (all kernels launched for it), averaged over the steps in which the same
-        pack ran; spread over the units of all packs.  Only launches tied to a unit count."""
-        cls, ps, un, ms = rec
-        step, prev_pass, acc = 0, 0, {}
-        for p_, u, m in zip(ps, un, ms):                # launches come in step order: forward, then backward
-            if p_ == 0 and prev_pass == 1:
-                step += 1
-            prev_pass = p_
-            if u >= 0:
-                key = (int(p_), step % n_packs, int(u))
-                tot, cnt = acc.get(key, (0.0, set()))
-                cnt.add(step)
-                acc[key] = (tot + float(m), cnt)
+        """Time of each scheduling unit (all kernels launched for it, averaged over the steps in which its pack ran):
+        spread over the units of all packs together, and the coefficient of variation inside each pack (the packs
+        differ in total work, so only that says how even one pack's units are)."""
+        ut = unit_times(rec)
         out = {}
         for name, pss in (("fwd", 0), ("bwd", 1)):
-            xs = [tot / len(cnt) for (p_, _, _), (tot, cnt) in acc.items() if p_ == pss]
-            if xs:
-                out[name] = _spread(xs)
+            xs = [v_ for (p_, _, _), v_ in ut.items() if p_ == pss]
+            if not xs:
+                continue
+            out[name] = _spread(xs)
+            per_pack = [_spread([v_ for (p_, i_, _), v_ in ut.items() if p_ == pss and i_ == i]) for i in range(n_packs)]
+            out[name]["cv_within_pack"] = [round(x["cv"], 4) for x in per_pack if x]
+            out[name]["max_over_mean_within_pack"] = [round(x["max_ms"] * x["n_units"] / sum_ms, 4) for x, sum_ms in
+                                                      ((x, x["n_units"] * x["mean_ms"]) for x in per_pack if x)]
         return out
 
     main_flags = S.FLAG_PER_UNIT_LAUNCH if args.per_unit else 0

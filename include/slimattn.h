@@ -85,7 +85,7 @@ typedef struct slimattn_params {
   int32_t total_tokens;      /* T */
   int32_t n_q_heads;         /* Hq */
   int32_t n_kv_heads;        /* Hkv, divides Hq */
-  int32_t head_dim;          /* d: 64 or 128 (bf16; T*Hq*d*2 must stay below 2 GiB); 16, 32, 64 or 128 (f32) */
+  int32_t head_dim;          /* d: 64 or 128 (bf16); 16, 32, 64 or 128 (f32); see slimattn_shape_supported */
   int32_t dtype;             /* SLIMATTN_F32 or SLIMATTN_BF16 */
   float   scale;             /* softmax scale applied to q.k */
   int32_t unit_lo, unit_hi;  /* run units [unit_lo, unit_hi) of the pass's list; unit_hi = -1 means all */
@@ -237,6 +237,13 @@ size_t slimattn_bwd_workspace_bytes(const slimattn_tables* t, int32_t n_q_heads,
                                     int32_t head_dim);
 
 /* ---- compute ------------------------------------------------------------------------------- */
+
+/* Whether slimattn_fwd / slimattn_bwd accept a pack of this shape (host only; what they check themselves).
+ * bf16: one sample's rows must stay below 2 GiB (max_sample_len * Hq * d * 2 < 2^31: tiles are addressed by
+ * 32-bit offsets from the sample's or the key tile's first row), and total_tokens * Hq * 16 < 2^31 (row
+ * statistics); the pack as a whole may exceed 2 GiB per tensor.  OK or EINVAL. */
+int slimattn_shape_supported(int64_t total_tokens, int32_t max_sample_len, int32_t n_q_heads, int32_t n_kv_heads,
+                             int32_t head_dim, int32_t dtype);
 
 /* Forward over units [unit_lo, unit_hi) of the forward list (paper: PackFlow Pipeline Parallelism
  * Scheduling, slice-level causal attention with a KV cache): for every query row i of every slice in

@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -72,6 +72,7 @@ def load_library():
     lib.slimattn_dag_timeline.argtypes = [C.c_int32, i64p, C.c_int32, i32p, i32p, i64p, i64p, i64p]
     lib.slimattn_dag_build_1f1b.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i64p, i64p,
                                             i32p, i64p, C.c_int32, i32p, i32p, i32p, i32p, C.c_int32, i32p]
+    lib.slimattn_shape_supported.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.slimattn_slice_pairs.argtypes = [vp]
     lib.slimattn_slice_pairs.restype = C.c_int64
     for f in (lib.slimattn_flops_fwd, lib.slimattn_flops_bwd):
@@ -261,6 +262,10 @@ def validate(cu, slices, unit_ptr, unit_slices, mode: int = CHECK_FORWARD) -> Tu
     rc = lib.slimattn_validate(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(up), _p(us), len(up) - 1, mode,
                                C.byref(rule))
     return rc, (rule.value or b"").decode()
+
+
+def shape_supported(total_tokens: int, max_sample_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int) -> bool:
+    return load_library().slimattn_shape_supported(total_tokens, max_sample_len, n_q_heads, n_kv_heads, head_dim, dtype) == 0
 
 
 def slice_pairs(rec) -> int:

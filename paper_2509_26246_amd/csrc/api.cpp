@@ -42,14 +42,10 @@ bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15
 
 int check_common(const slimattn_params* p, const slimattn_tables* t, int pass, int* lo, int* hi) {
   if (!p || !t) return SLIMATTN_EINVAL;
-  if (p->dtype != SLIMATTN_F32 && p->dtype != SLIMATTN_BF16) return SLIMATTN_EINVAL;
-  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0 || p->n_q_heads > 65535) return SLIMATTN_EINVAL;
-  const int d = p->head_dim;
-  if (p->dtype == SLIMATTN_BF16 ? !(d == 64 || d == 128) : !(d == 16 || d == 32 || d == 64 || d == 128)) return SLIMATTN_EINVAL;
   if ((int64_t)p->total_tokens != t->total_tokens) return SLIMATTN_EINVAL;
+  const int rc = slimattn_shape_supported(p->total_tokens, t->max_sample_len, p->n_q_heads, p->n_kv_heads, p->head_dim, p->dtype);
+  if (rc != SLIMATTN_OK) return rc;
   if (!(p->scale == p->scale)) return SLIMATTN_EINVAL;
-  // the bf16 kernels address tiles with 32-bit byte offsets from a sample's first row
-  if (p->dtype == SLIMATTN_BF16 && (int64_t)p->total_tokens * p->n_q_heads * d * 2 >= (int64_t(1) << 31)) return SLIMATTN_EINVAL;
   *lo = p->unit_lo;
   *hi = p->unit_hi < 0 ? t->n_units[pass] : p->unit_hi;
   if (*lo < 0 || *hi > t->n_units[pass] || *lo > *hi) return SLIMATTN_EINVAL;
@@ -103,6 +99,26 @@ int prepare_static_scratch() {
 using namespace slimattn;
 
 extern "C" {
+
+int slimattn_shape_supported(int64_t total_tokens, int32_t max_sample_len, int32_t n_q_heads, int32_t n_kv_heads,
+                             int32_t head_dim, int32_t dtype) {
+  if (dtype != SLIMATTN_F32 && dtype != SLIMATTN_BF16) return SLIMATTN_EINVAL;
+  if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 || n_q_heads > 65535) return SLIMATTN_EINVAL;
+  const int d = head_dim;
+  if (dtype == SLIMATTN_BF16 ? !(d == 64 || d == 128) : !(d == 16 || d == 32 || d == 64 || d == 128)) return SLIMATTN_EINVAL;
+  if (total_tokens < 0 || total_tokens > INT32_MAX || max_sample_len < 0 || max_sample_len > total_tokens) return SLIMATTN_EINVAL;
+  if (dtype == SLIMATTN_BF16) {
+    // The bf16 kernels address tile rows with 32-bit byte offsets from a base that moves with the work item: the
+    // sample's first row (K, V, with Hkv heads per row) or the key tile's first row (Q, dO, with Hq heads per
+    // row).  The largest offset is therefore one sample's rows times the wider row, and it has to stay below
+    // 2^31 (the offsets are formed in signed 32-bit arithmetic).  The pack as a whole may be larger: pointers
+    // to a work item's base are 64-bit.
+    if ((int64_t)max_sample_len * n_q_heads * d * 2 >= (int64_t(1) << 31)) return SLIMATTN_EINVAL;
+    // row statistics of the backward pass: 16 bytes per (head, token), one 32-bit offset from the array's start
+    if (total_tokens * n_q_heads * 16 >= (int64_t(1) << 31)) return SLIMATTN_EINVAL;
+  }
+  return SLIMATTN_OK;
+}
 
 int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v, const slimattn_tables* t,
                  void* o, float* lse, void* stream) {

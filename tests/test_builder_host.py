@@ -226,3 +226,24 @@ def test_native_solver_candidates_and_full_size():
     with pytest.raises(S.SlimAttnError) as e:
         S.solve_partition([100], m_fwd=2, m_bwd=2, token_cap_fwd=10, granule=5)
     assert e.value.code == -7
+
+
+def test_shape_limits_are_per_sample_not_per_pack():
+    """The bf16 kernels form 32-bit byte offsets from a work item's base (the sample's first row for K/V, the key tile's
+    first row for Q/dO), so what must stay below 2^31 is one sample's extent, max_len * Hq * d * 2; the pack may be larger."""
+    ok = lambda *a: S.shape_supported(*a)
+    # 32 heads of 128: a row is 8192 bytes; 2^31 / 8192 = 262144 rows
+    assert ok(262143, 262143, 32, 8, 128, S.BF16) and not ok(262144, 262144, 32, 8, 128, S.BF16)
+    assert ok(1_000_000, 8192, 32, 8, 128, S.BF16)                   # an 8 GB q tensor of short samples
+    assert ok(411_398, 262_144, 16, 4, 128, S.BF16)                  # the extreme-skew workload
+    assert not ok(5_000_000, 1000, 32, 8, 128, S.BF16)               # row statistics: T * Hq * 16 must stay below 2^31
+    assert ok(4_194_303, 4_194_303, 1, 1, 128, S.BF16) and not ok(8_388_608, 8_388_608, 1, 1, 128, S.BF16)
+    assert ok(10_000_000, 10_000_000, 64, 8, 128, S.F32)             # the fp32 kernels index with 64-bit arithmetic
+    for bad in ((10, 10, 3, 2, 128, S.BF16), (10, 10, 4, 2, 96, S.BF16), (10, 11, 4, 2, 64, S.BF16), (10, 10, 4, 2, 64, 9),
+                (-1, 0, 4, 2, 64, S.BF16), (10, 10, 4, 2, 256, S.F32)):
+        assert not ok(*bad), bad
+    # the largest offsets the kernels form, recomputed here: K/V rows of a sample from its start, Q/dO rows from a key
+    # tile's start to the sample's end, and the per-step range of the dK/dV kernel
+    for T_, Lmax, hq, hkv, d in ((411_398, 262_144, 16, 4, 128), (262_143, 262_143, 32, 8, 128), (1_000_000, 8192, 32, 8, 128)):
+        assert ok(T_, Lmax, hq, hkv, d, S.BF16)
+        assert Lmax * hkv * d * 2 < 2 ** 31 and Lmax * hq * d * 2 < 2 ** 31 and T_ * hq * 16 < 2 ** 31

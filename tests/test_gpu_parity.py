@@ -259,10 +259,10 @@ def _sq_sum(x, axes):
     return (x.astype(np.float64) ** 2).sum(axes)
 
 
-def _conservation(L, cu, q, k, dO, dq, dk, dv, hkv, g, chunk=16384):
-    """Largest error of (V) and (K) over all samples, in units of the rms error the roundings imply."""
+def _conservation(L, cu, q, k, dO, dq, dk, dv, hkv, g, chunk=16384, samples=None):
+    """Largest error of (V) and (K) over all (or the listed) samples, in units of the rms error the roundings imply."""
     worst_v = worst_k = 0.0
-    for s in range(len(L)):
+    for s in (range(len(L)) if samples is None else samples):
         a, b = int(cu[s]), int(cu[s + 1])
         if b == a:
             continue
@@ -363,6 +363,52 @@ def test_full_size_sampled_rows_and_identities(name, modes):
         # O, lse, dQ: one block per row, same order in both modes; dK/dV: other summation order
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
         assert np.max(np.abs(a[3] - b[3])) <= TOL_G and np.max(np.abs(a[4] - b[4])) <= TOL_G
+
+
+def test_pack_larger_than_2gib_per_tensor():
+    """80 samples of 4096 rows with 32 query heads of 128: q, o, dO, dQ are 2.7 GB each, so rows of the later samples lie
+    beyond 2^31 bytes from the tensors' start (what has to stay below 2^31 is one sample's extent).  Sampled rows and key
+    rows of the last sample, of the sample that straddles the 2 GiB mark and of the first one; conservation laws there."""
+    hq, hkv, d, n, Ls = 32, 8, 128, 80, 4096
+    assert n * Ls * hq * d * 2 > 2 ** 31 and S.shape_supported(n * Ls, Ls, hq, hkv, d, S.BF16)
+    L = [Ls] * n
+    T_ = n * Ls
+    r = np.random.default_rng(7)
+    q, k, v, dO = [W.bf16_round(r.standard_normal((T_, h, d), dtype=np.float32) * np.float32(sc))
+                   for h, sc in ((hq, 0.5), (hkv, 0.5), (hkv, 0.5), (hq, 0.1))]
+    print("inputs drawn", flush=True)
+    cu, sl, fu, bu = _tables(L, 2048, ("PREFIX_FILL", {"m": 16, "w_quad": 2, "w_lin": 0}),
+                             ("PREFIX_FILL", {"m": 24, "w_quad": 5, "w_lin": 0, "backward": True}))
+    scale = d ** -0.5
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
+    straddle = (2 ** 31) // (hq * d * 2 * Ls)                   # the sample holding the row at byte offset 2^31
+    picks = [0, straddle, n - 1]
+    rows = np.concatenate([[cu[s], cu[s] + 1, cu[s + 1] - 1] + r.integers(cu[s], cu[s + 1], 6).tolist() for s in picks]).astype(np.int64)
+    heads = r.integers(0, hq, len(rows))
+    ro, rl = A.fwd_rows(q, k, v, cu, scale, rows, heads)
+    rdq = A.dq_rows(q, k, v, dO, cu, scale, rows, heads)
+    want = []
+    for s in picks:
+        keys = np.unique(np.concatenate([[cu[s], cu[s + 1] - 1], r.integers(cu[s], cu[s + 1], 10)]))
+        want.append((s, keys) + A.dkdv_rows(q, k, v, dO, cu, scale, s, hkv - 1, keys))
+    print("oracle rows done", flush=True)
+    results = []
+    for flags in (0, S.FLAG_PER_UNIT_LAUNCH):
+        _poison(prob)
+        prob.forward(flags=flags); prob.backward(flags=flags); torch.cuda.synchronize()
+        o, lse = H.device_to_f32(prob.o), prob.lse.cpu().numpy()
+        dq, dk, dv = H.device_to_f32(prob.dQ), H.device_to_f32(prob.dK), H.device_to_f32(prob.dV)
+        assert np.max(np.abs(o[rows, heads] - ro)) <= TOL_O and np.max(np.abs(lse[heads, rows] - rl)) <= TOL_O
+        assert np.max(np.abs(dq[rows, heads] - rdq)) <= TOL_G
+        for s, keys, rdk, rdv in want:
+            assert np.max(np.abs(dk[keys, hkv - 1] - rdk)) <= TOL_G and np.max(np.abs(dv[keys, hkv - 1] - rdv)) <= TOL_G, (flags, s)
+        wv, wk = _conservation(L, cu, q, k, dO, dq, dk, dv, hkv, hq // hkv, samples=picks + [1, n - 2])
+        assert wv <= kSigmas and wk <= kSigmas, (flags, wv, wk)
+        for x in (o, dq, dk, dv):
+            assert np.isfinite(x[-Ls:]).all() and np.isfinite(x[:Ls]).all()
+        results.append((prob.o.view(torch.int16).clone(), prob.dQ.view(torch.int16).clone()))
+        del o, dq, dk, dv
+    assert torch.equal(results[0][0], results[1][0]) and torch.equal(results[0][1], results[1][1])
 
 
 def test_bf16_non_uniform_slice_bounds():
