@@ -87,6 +87,22 @@ int timed(int cls, void* stream, F&& launch) {
   return e;
 }
 
+// The whole call between two events on the caller's stream (the gaps between its launches included, so this is
+// the time a caller sees, not the sum of the kernels' times).
+template <class F>
+int timed_call(int cls, void* stream, F&& body) {
+  if (!g_prof.on) return body();
+  if (g_prof.used >= g_prof.start.size()) { ++g_prof.dropped; return body(); }
+  const size_t i = g_prof.used++;
+  g_prof.cls[i] = cls;
+  g_prof.pass[i] = g_prof.cur_pass;
+  g_prof.unit[i] = -1;
+  (void)hipEventRecord(g_prof.start[i], (hipStream_t)stream);
+  const int rc = body();
+  (void)hipEventRecord(g_prof.stop[i], (hipStream_t)stream);
+  return rc;
+}
+
 }  // namespace
 
 int prepare_static_scratch() {
@@ -120,6 +136,9 @@ int slimattn_shape_supported(int64_t total_tokens, int32_t max_sample_len, int32
   return SLIMATTN_OK;
 }
 
+static int fwd_impl(const slimattn_params* p, const void* q, const void* k, const void* v, const slimattn_tables* t, void* o,
+                    float* lse, void* stream, int lo, int hi);
+
 int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v, const slimattn_tables* t,
                  void* o, float* lse, void* stream) {
   int lo, hi;
@@ -127,6 +146,14 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
   if (rc != SLIMATTN_OK) return rc;
   if (t->total_tokens == 0 || lo == hi) return SLIMATTN_OK;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return SLIMATTN_EINVAL;
+  g_prof.cur_pass = 0;
+  g_prof.cur_unit = -1;
+  return timed_call(SLIMATTN_K_FWD_CALL, stream, [&] { return fwd_impl(p, q, k, v, t, o, lse, stream, lo, hi); });
+}
+
+static int fwd_impl(const slimattn_params* p, const void* q, const void* k, const void* v, const slimattn_tables* t, void* o,
+                    float* lse, void* stream, int lo, int hi) {
+  int rc = SLIMATTN_OK;
   const int z = tile_index(fwd_q_tile(p->dtype, p->head_dim));
   const LaunchCtx ctx{p, stream, t->total_tokens};
   auto run = [&](const QItem* items, int n) -> int {
@@ -152,6 +179,10 @@ int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const v
   return SLIMATTN_OK;
 }
 
+static int bwd_impl(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                    const void* dO, const slimattn_tables* t, void* dQ, void* dK, void* dV, void* workspace, void* stream, int lo,
+                    int hi);
+
 int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o, const float* lse,
                  const void* dO, const slimattn_tables* t, void* dQ, void* dK, void* dV, void* workspace, void* stream) {
   int lo, hi;
@@ -161,6 +192,16 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dO) ||
       !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return SLIMATTN_EINVAL;
+  g_prof.cur_pass = 1;
+  g_prof.cur_unit = -1;
+  return timed_call(SLIMATTN_K_BWD_CALL, stream,
+                    [&] { return bwd_impl(p, q, k, v, o, lse, dO, t, dQ, dK, dV, workspace, stream, lo, hi); });
+}
+
+static int bwd_impl(const slimattn_params* p, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                    const void* dO, const slimattn_tables* t, void* dQ, void* dK, void* dV, void* workspace, void* stream, int lo,
+                    int hi) {
+  int rc = SLIMATTN_OK;
   const bool f32 = p->dtype == SLIMATTN_F32;
   const size_t T = (size_t)t->total_tokens;
   const size_t acc_elems = T * p->n_kv_heads * p->head_dim;
@@ -171,20 +212,21 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
   void* stat3 = (char*)delta + align_up(T * p->n_q_heads * sizeof(float));
   float* parts = (float*)((char*)stat3 + align_up(T * p->n_q_heads * 16));              // partial tiles of divided key tiles
   const int sc = split_class(p->n_kv_heads);
-  const LaunchCtx ctx{p, stream, t->total_tokens};
   const int n_units = t->n_units[1];
   const bool whole = lo == 0 && hi == n_units;
-  g_prof.cur_pass = 1;
-  g_prof.cur_unit = -1;
   const bool per_unit = (p->flags & SLIMATTN_FLAG_PER_UNIT_LAUNCH) != 0;
 
+  const LaunchCtx ctx{p, stream, t->total_tokens};
+
   // Row statistic delta_i = dO_i . o_i, always for the query rows of the launch scope only (a caller that runs the
-  // list one unit at a time need not have o, lse and dO of later units yet).  fp32: a prepass in front of each
-  // dQ launch.  bf16: normally the dQ kernel computes it for the rows it owns and stores it (with lse in log2
-  // units, both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it.
-  // With a very long sample (its K and V, over all KV heads, far beyond what the caches hold) the dQ blocks
-  // depend on streaming the same K/V tiles at the same time, and the longer prologue cost 9 % there
-  // (256K sample); then a prepass stores the statistics, as in fp32 mode.
+  // list one unit at a time need not have o, lse and dO of later units yet).  fp32: a prepass in front of each dQ
+  // launch.  bf16: normally the dQ kernel computes it for the rows it owns and stores it (with lse in log2 units,
+  // both as bf16 triples) for the dK/dV launch of the same scope, which therefore runs after it; with a very
+  // long sample (its K and V, over all KV heads, far beyond what the caches hold) the dQ blocks depend on
+  // streaming the same K/V tiles at the same time, and the longer prologue cost 9 % there (256K sample), so
+  // the prepass is kept.  (The dQ launch on a second stream beside the dK/dV launch, with the statistics always
+  // from the prepass, was measured: the two kernels cannot share a compute unit and only slow each other --
+  // 32K pack, fused 928 -> 893 TFLOP/s, per-unit 734 -> 716 -- so every launch stays on the caller's stream.)
   const bool own_stats = !f32 && !(p->flags & SLIMATTN_FLAG_STATS_PREPASS) &&
                          (size_t)t->max_sample_len * p->n_kv_heads * p->head_dim * 4 <= (size_t(128) << 20);
   const int zq = tile_index(dq_q_tile(p->dtype, p->head_dim));
@@ -223,37 +265,35 @@ int slimattn_bwd(const slimattn_params* p, const void* q, const void* k, const v
       return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[ti][sc] + ra, rb - ra, tile_rows);
     });
   };
+  auto finish = [&](int e) -> int { return hip_rc(e); };
 
   if (whole && !per_unit) {
     // One scope holding every slice: each key tile's owner sums all later query rows itself and
     // writes dK/dV directly; the fp32 accumulators in the workspace are not touched.
-    rc = hip_rc(run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size()));
-    if (rc != SLIMATTN_OK) return rc;
-    return hip_rc(f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs)
-                      : run_dkdv_split(t->fused, t->d_fused, 0));
+    int e = run_dq(t->d_fused.q_items[zq], (int)t->fused.q_items[zq].size());
+    if (e == 0)
+      e = f32 ? run_dkdv(t->d_fused.kv_items[zk], (int)t->fused.kv_items[zk].size(), t->d_fused.segs)
+              : run_dkdv_split(t->fused, t->d_fused, 0);
+    return finish(e);
   }
 
   const auto& qoff = t->per_unit[1].q_off[zq];
   const auto& koff = t->per_unit[1].kv_off[zk];
-  if (!per_unit) {
-    rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[lo], qoff[hi] - qoff[lo]));
-    if (rc != SLIMATTN_OK) return rc;
-  }
-  for (int u = lo; u < hi; ++u) {
-    // Units run one after another on the stream; each adds its queries' contributions to every key tile of the
-    // prefix it sees.  The tile's single owner block continues from the fp32 accumulator an earlier unit left
-    // (the tile's first unit starts from zero, so nothing has to be cleared) and the tile's last unit writes
-    // dK/dV themselves: the summation order is the unit order, and a tile is released as soon as it is complete.
+  int e = 0;
+  if (!per_unit) e = run_dq(t->d_per_unit[1].q_items[zq] + qoff[lo], qoff[hi] - qoff[lo]);
+  for (int u = lo; u < hi && e == 0; ++u) {
+    // Units run one after another on the stream; each adds its queries' contributions to every key row of the
+    // prefix it sees.  A row's single owner block continues from the fp32 accumulator an earlier unit left
+    // (the row's first unit starts from zero, so nothing has to be cleared) and the row's last unit writes
+    // dK/dV themselves: the summation order is the unit order, and a row is released as soon as it is complete.
     g_prof.cur_unit = u;
-    if (per_unit) {
-      rc = hip_rc(run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]));
-      if (rc != SLIMATTN_OK) return rc;
-    }
-    rc = hip_rc(f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs)
-                    : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u));
-    if (rc != SLIMATTN_OK) return rc;
+    if (per_unit) e = run_dq(t->d_per_unit[1].q_items[zq] + qoff[u], qoff[u + 1] - qoff[u]);
+    if (e == 0)
+      e = f32 ? run_dkdv(t->d_per_unit[1].kv_items[zk] + koff[u], koff[u + 1] - koff[u], t->d_per_unit[1].segs)
+              : run_dkdv_split(t->per_unit[1], t->d_per_unit[1], u);
   }
   g_prof.cur_unit = -1;
+  rc = finish(e);
   return rc;
 }
 

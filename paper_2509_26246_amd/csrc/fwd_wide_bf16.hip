@@ -24,9 +24,10 @@
 // register block that holds it (no initialisation, no vector instructions), so the products deliver the
 // exponents.  The
 // exponentials of a unit are taken against the reference as it stands; when the unit is done and before
-// its probabilities are used, one wave-uniform test asks whether any score exceeded the reference by more
-// than 2^8, and only then the reference moves: accumulators and row sums are rescaled, the unit's
-// probabilities recomputed from its scores (still in their registers) and the next unit's scores shifted.
+// its probabilities are used, one wave-uniform test asks whether any lane's sum of the unit's 16 probabilities
+// of a head exceeded 2^12 (an overflow to inf trips it too), and only then the reference moves: accumulators and
+// row sums are rescaled, the unit's probabilities recomputed from its scores (still in their registers) and the
+// next unit's scores shifted.
 //
 // Hazards of the inline-asm products: see dkdv_wide_bf16.hip; here their results (O^T) are read only by
 // later products on the same accumulator, and after explicit wait states in the rescaling path and the
