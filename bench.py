@@ -176,7 +176,7 @@ def main():
         return r["cu"], r["slices"], r["fwd"], r["bwd"]
 
     def make_problems(table_fn):
-        probs, pairs, tabs, build_ms = [], [], [], {"slices_and_units": [], "derive_and_upload": []}
+        probs, pairs, tabs, build_ms = [], [], [], {"slices_and_units": [], "derive_and_upload": [], "derive_and_queue_upload": []}
         for L, q, k, v, dO in packs:
             t0 = time.perf_counter()
             cu, sl, fu, bu = table_fn(L)
@@ -185,8 +185,14 @@ def main():
             tmp = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1])      # timed on its own: derived work-lists + one upload
             t2 = time.perf_counter()
             tmp.destroy()
+            t3 = time.perf_counter()
+            tmp = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1], stream=torch.cuda.current_stream().cuda_stream)
+            t4 = time.perf_counter()                                       # host time when the upload is queued on the stream
+            torch.cuda.synchronize()
+            tmp.destroy()
             build_ms["slices_and_units"].append((t1 - t0) * 1e3)
             build_ms["derive_and_upload"].append((t2 - t1) * 1e3)
+            build_ms["derive_and_queue_upload"].append((t4 - t3) * 1e3)
             probs.append(H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=(w.dtype == "bf16")))
             pairs.append(int(sum(S.slice_pairs(r) for r in sl)))
             tabs.append((cu, sl, fu, bu))

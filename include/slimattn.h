@@ -224,6 +224,15 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
                            const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
                            const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
                            slimattn_tables** out);
+/* The same with the upload queued on `stream` (use_stream != 0; NULL = the default stream) instead of a
+ * synchronous copy: the host returns without waiting (the paper overlaps the solver with data loading so that
+ * the compute stream never waits for a packing plan; Zero-Overhead Runtime Integration), and compute calls
+ * queued on the same stream afterwards see the tables.  A compute call on another stream must be ordered after
+ * the upload by the caller.  The handle keeps a pinned staging copy until it is destroyed. */
+int slimattn_tables_create_async(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                                 const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
+                                 const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
+                                 void* stream, int use_stream, slimattn_tables** out);
 void slimattn_tables_destroy(slimattn_tables* t);
 
 /* Counts held by a handle: what = 0 tokens, 1 samples, 2 slices, 3 forward units, 4 backward units,

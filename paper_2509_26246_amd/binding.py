@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create", "slimattn_tables_create_async",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -80,6 +80,8 @@ def load_library():
         f.restype = C.c_int64
     lib.slimattn_tables_create.argtypes = [i32p, C.c_int32, vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32,
                                            C.POINTER(vp)]
+    lib.slimattn_tables_create_async.argtypes = [i32p, C.c_int32, vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32,
+                                                 vp, C.c_int, C.POINTER(vp)]
     lib.slimattn_tables_destroy.argtypes = [vp]
     lib.slimattn_tables_destroy.restype = None
     lib.slimattn_tables_count.argtypes = [vp, C.c_int]
@@ -303,16 +305,22 @@ class Tables:
             pass
 
 
-def tables_create(cu, slices, fwd_unit_ptr, fwd_unit_slices, bwd_unit_ptr, bwd_unit_slices) -> Tables:
+def tables_create(cu, slices, fwd_unit_ptr, fwd_unit_slices, bwd_unit_ptr, bwd_unit_slices, stream=False) -> Tables:
+    """slimattn_tables_create, or slimattn_tables_create_async when `stream` is given (a hipStream_t address, or
+    None for the default stream): the upload is then queued on that stream and the host does not wait."""
     lib = load_library()
     cu, slices = _i32(cu), _i32(slices).reshape(-1, 8)
     fp, fs, bp, bs = _i32(fwd_unit_ptr), _i32(fwd_unit_slices), _i32(bwd_unit_ptr), _i32(bwd_unit_slices)
     h = C.c_void_p()
-    rc = lib.slimattn_tables_create(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(fp), _p(fs), len(fp) - 1,
-                                    _p(bp), _p(bs), len(bp) - 1, C.byref(h))
+    if stream is False:
+        rc = lib.slimattn_tables_create(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(fp), _p(fs), len(fp) - 1,
+                                        _p(bp), _p(bs), len(bp) - 1, C.byref(h))
+    else:
+        rc = lib.slimattn_tables_create_async(_p(cu), len(cu) - 1, slices.ctypes.data, len(slices), _p(fp), _p(fs), len(fp) - 1,
+                                              _p(bp), _p(bs), len(bp) - 1, stream, 1, C.byref(h))
     if rc != 0:
         extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
-        raise SlimAttnError(rc, "slimattn_tables_create", extra)
+        raise SlimAttnError(rc, "slimattn_tables_create", "slimattn_tables_create_async", extra)
     return Tables(h.value, len(fp) - 1, len(bp) - 1, int(cu[-1]))
 
 

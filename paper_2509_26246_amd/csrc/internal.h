@@ -96,6 +96,7 @@ struct slimattn_tables {
   const int32_t* d_cu = nullptr;
   const slimattn_slice* d_slices = nullptr;
   void* d_blob = nullptr;
+  void* h_staging = nullptr;      // pinned copy of the tables for an upload queued on a stream (kept until destroy)
   int device = -1;
 };
 

@@ -178,6 +178,14 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
                            const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
                            const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
                            slimattn_tables** out) {
+  return slimattn_tables_create_async(cu, n, slices, n_slices, fwd_unit_ptr, fwd_unit_slices, n_fwd_units, bwd_unit_ptr,
+                                      bwd_unit_slices, n_bwd_units, nullptr, 0, out);
+}
+
+int slimattn_tables_create_async(const int32_t* cu, int32_t n, const slimattn_slice* slices, int32_t n_slices,
+                                 const int32_t* fwd_unit_ptr, const int32_t* fwd_unit_slices, int32_t n_fwd_units,
+                                 const int32_t* bwd_unit_ptr, const int32_t* bwd_unit_slices, int32_t n_bwd_units,
+                                 void* stream, int use_stream, slimattn_tables** out) {
   if (!out) return SLIMATTN_EINVAL;
   *out = nullptr;
   int rc = slimattn_validate(cu, n, slices, n_slices, fwd_unit_ptr, fwd_unit_slices, n_fwd_units, SLIMATTN_CHECK_FORWARD, nullptr);
@@ -255,11 +263,19 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
     hipError_t e = hipGetDevice(&t->device);
     if (e == hipSuccess) (void)prepare_static_scratch();    // set-up for slimattn_bwd_static on this device; its own call reports a failure
     if (e == hipSuccess) e = hipMalloc(&t->d_blob, blob.size());
-    if (e == hipSuccess) e = hipMemcpy(t->d_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !use_stream) e = hipMemcpy(t->d_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess && use_stream) {
+      // the copy is queued on the caller's stream from a pinned staging buffer that lives as long as the handle:
+      // launches queued on the same stream afterwards see the tables, and the host does not wait
+      e = hipHostMalloc(&t->h_staging, blob.size(), hipHostMallocDefault);
+      if (e == hipSuccess) {
+        std::memcpy(t->h_staging, blob.data(), blob.size());
+        e = hipMemcpyAsync(t->d_blob, t->h_staging, blob.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
+      }
+    }
     if (e != hipSuccess) {
       g_last_hip_error = (int)e;
-      if (t->d_blob) (void)hipFree(t->d_blob);
-      delete t;
+      slimattn_tables_destroy(t);
       return SLIMATTN_EHIP;
     }
     const char* base = (const char*)t->d_blob;
@@ -288,7 +304,8 @@ int slimattn_tables_create(const int32_t* cu, int32_t n, const slimattn_slice* s
 
 void slimattn_tables_destroy(slimattn_tables* t) {
   if (!t) return;
-  if (t->d_blob) (void)hipFree(t->d_blob);
+  if (t->d_blob) (void)hipFree(t->d_blob);      // (waits for work that may still read the tables)
+  if (t->h_staging) (void)hipHostFree(t->h_staging);
   delete t;
 }
 

@@ -430,6 +430,26 @@ def test_bf16_non_uniform_slice_bounds():
         _run_modes(prob, ref, TOL_O, TOL_G, f"bounds {hq}/{hkv}/{d}")
 
 
+def test_tables_uploaded_on_the_callers_stream():
+    # the tables' upload queued on a side stream, compute calls queued right behind it on the same stream
+    L = [300, 77, 1, 129]
+    cu, sl, fu, bu = _tables(L, 64, ("TOKEN_CAP", {"cap": 128}), ("PREFIX_FILL", {"m": 3, "w_quad": 5, "w_lin": 0, "backward": True}))
+    q, k, v, dO = _draw(sum(L), 4, 2, 128, 3, True, 0.5, 0.1)
+    ref = _oracle(q, k, v, dO, cu, 128 ** -0.5)
+    prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            prob.tables.destroy()
+            prob.tables = S.tables_create(cu, sl, fu[0], fu[1], bu[0], bu[1], stream=side.cuda_stream)
+            _poison(prob)
+            prob.forward(flags=S.FLAG_PER_UNIT_LAUNCH); prob.backward(flags=S.FLAG_PER_UNIT_LAUNCH)
+            prob.forward(); prob.backward()
+    side.synchronize()
+    _check(prob, ref, TOL_O, TOL_G, "async tables")
+
+
 def test_rejects_bad_arguments():
     L = [64]
     cu, sl, fu, bu = _tables(L, 64, ("ALL", {}), ("ALL", {}))
