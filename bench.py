@@ -140,6 +140,9 @@ def main():
     ap.add_argument("--per-unit", action="store_true", help="main measurement: one launch per unit instead of one fused launch")
     ap.add_argument("--seeds", default="", help="comma-separated subset of the workload's seeds (default: all four)")
     ap.add_argument("--brief", action="store_true", help="skip the per-seed and the secondary per-unit measurements")
+    ap.add_argument("--granule", type=int, default=0,
+                    help="solver partition: cuts on multiples of this many rows (default: the rows whose forward work "
+                         "items fill the chip once, 256 blocks x 128 rows / head pairs, at least 256)")
     ap.add_argument("--partition", choices=["policy", "solver"], default="policy",
                     help="slice table and unit lists of the main measurement: the workload's greedy policies on fixed-size "
                          "slices, or the exact min-max partition solver (same unit counts, cuts on 256-row granules)")
@@ -171,8 +174,12 @@ def main():
         _, _, fu, bu = policy_tables(L)
         wq_f, wl_f = w.fwd_policy[1].get("w_quad", 2), w.fwd_policy[1].get("w_lin", 0)
         wq_b, wl_b = w.bwd_policy[1].get("w_quad", 5), w.bwd_policy[1].get("w_lin", 0)
+        # Cuts on multiples of the rows that fill the chip once with forward work items (a query tile of 128 rows and a
+        # pair of heads per block, 256 blocks): a unit a little over such a multiple would leave a second round of
+        # blocks almost empty, and on long samples one round takes milliseconds.
+        granule = args.granule or max(256, 256 * 128 // max(1, w.n_q_heads // 2))
         r = S.solve_partition(L, m_fwd=len(fu[0]) - 1, m_bwd=len(bu[0]) - 1, w_quad_fwd=wq_f, w_lin_fwd=wl_f, w_quad_bwd=wq_b,
-                              w_lin_bwd=wl_b, granule=256, max_slice=w.slice_size)
+                              w_lin_bwd=wl_b, granule=granule, max_slice=max(w.slice_size, granule))
         return r["cu"], r["slices"], r["fwd"], r["bwd"]
 
     def make_problems(table_fn):
