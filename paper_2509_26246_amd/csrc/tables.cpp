@@ -107,8 +107,9 @@ void append_split(ScopeLists& L, int ti, const std::vector<KvItem>& ki, const st
 }
 
 // `row_marks(sample)`: {load_until, final_from} of the sample's key rows for this scope.
+// want_kv: key-tile lists are only needed by the backward pass.
 template <class Marks>
-void append_scope(ScopeLists& L, const std::vector<Run>& runs, Marks&& row_marks) {
+void append_scope(ScopeLists& L, const std::vector<Run>& runs, bool want_kv, Marks&& row_marks) {
   const int32_t seg_base = (int32_t)L.segs.size();
   for (const Run& r : runs) L.segs.push_back(Seg{r.q_lo, r.q_hi});
   for (int z = 0; z < kNumTileSizes; ++z) {
@@ -126,7 +127,7 @@ void append_scope(ScopeLists& L, const std::vector<Run>& runs, Marks&& row_marks
     // key tiles: per sample, prefix [kv_start, last run's end); heavy-first by query rows at or after the tile
     std::vector<KvItem> ki;
     std::vector<int64_t> weight;
-    size_t i = is_key_tile(B) ? 0 : runs.size();
+    size_t i = (want_kv && is_key_tile(B)) ? 0 : runs.size();
     while (i < runs.size()) {
       size_t j = i;
       while (j < runs.size() && runs[j].sample == runs[i].sample) ++j;
@@ -223,7 +224,7 @@ int slimattn_tables_create_async(const int32_t* cu, int32_t n, const slimattn_sl
         }
       for (int32_t u = 0; u < t->n_units[pass]; ++u) {
         const int32_t a = t->unit_ptr[pass][u], b = t->unit_ptr[pass][u + 1];
-        append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a),
+        append_scope(t->per_unit[pass], merge_runs(slices, t->unit_slices[pass].data() + a, b - a), pass == 1,
                      [&](int32_t sample) -> std::pair<int32_t, int32_t> {
                        int32_t before = 0, after = 0;      // furthest reach of an earlier / a later unit (0: none)
                        for (const auto& ur : reach[sample]) {
@@ -239,7 +240,7 @@ int slimattn_tables_create_async(const int32_t* cu, int32_t n, const slimattn_sl
     for (int z = 0; z < kNumTileSizes; ++z) { t->fused.q_off[z].push_back(0); t->fused.kv_off[z].push_back(0); }
     for (int ti = 0; ti < kNumSplitTiles; ++ti)
       for (int c = 0; c < kNumSplitClasses; ++c) { t->fused.split_off[ti][c].push_back(0); t->fused.reduce_off[ti][c].push_back(0); }
-    append_scope(t->fused, merge_runs(slices, all.data(), n_slices),
+    append_scope(t->fused, merge_runs(slices, all.data(), n_slices), true,
                  [](int32_t) -> std::pair<int32_t, int32_t> { return {0, 0}; });
 
     // one blob, one upload
