@@ -320,7 +320,7 @@ def tables_create(cu, slices, fwd_unit_ptr, fwd_unit_slices, bwd_unit_ptr, bwd_u
                                               _p(bp), _p(bs), len(bp) - 1, stream, 1, C.byref(h))
     if rc != 0:
         extra = f" hip={lib.slimattn_last_hip_error()}" if rc == -4 else ""
-        raise SlimAttnError(rc, "slimattn_tables_create", "slimattn_tables_create_async", extra)
+        raise SlimAttnError(rc, "slimattn_tables_create", extra)
     return Tables(h.value, len(fp) - 1, len(bp) - 1, int(cu[-1]))
 
 
