@@ -273,16 +273,25 @@ def main():
         every stage holds one such attention layer, per number of stages (mean over the packs)."""
         ut = unit_times(rec)
         out = {}
+        # what one attention layer keeps per token between its tasks: K and V (bf16) as the cache, the fp32 rows
+        # dK and dV are accumulated in until their release, and q, o (bf16) and lse from forward to backward
+        kv_b, grad_b, act_b = 2 * hkv * d * 2, 2 * hkv * d * 4, 2 * hq * d * 2 + hq * 4
         for stages in (1, 2, 4, 8):
             tot, busy = 0.0, 0.0
+            mem = {"kv_state_per_slice": 0.0, "kv_state_per_sample": 0.0, "with_activations_per_slice": 0.0, "with_activations_per_sample": 0.0}
             for i, (cu, sl, fu, bu) in enumerate(tabs):
                 fc = [int(round(ut[(0, i, u)] * 1e6)) for u in range(len(fu[0]) - 1)]      # ns
                 bc = [int(round(ut[(1, i, u)] * 1e6)) for u in range(len(bu[0]) - 1)]
                 g = S.dag_build_1f1b(sl, fu, bu, stages, fc, bc)
-                _, _, t_total = S.dag_timeline(g["weight"], g["edge_from"], g["edge_to"])
+                start, finish, t_total = S.dag_timeline(g["weight"], g["edge_from"], g["edge_to"])
                 tot += t_total * 1e-6
                 busy += (sum(fc) + sum(bc)) * 1e-6
-            out[str(stages)] = {"makespan_ms": tot / n_packs, "idle_share": 1.0 - busy / tot if tot > 0 else 0.0}
+                for key, act, per_slice in (("kv_state_per_slice", 0, True), ("kv_state_per_sample", 0, False),
+                                            ("with_activations_per_slice", act_b, True), ("with_activations_per_sample", act_b, False)):
+                    peak, _ = S.dag_memory(start, finish, S.dag_buffers_1f1b(sl, fu, bu, stages, act, kv_b, grad_b, per_slice), stages)
+                    mem[key] += float(peak.max()) / 2 ** 20
+            out[str(stages)] = {"makespan_ms": tot / n_packs, "idle_share": 1.0 - busy / tot if tot > 0 else 0.0,
+                                "peak_mib_worst_stage": {k_: round(v_ / n_packs, 1) for k_, v_ in mem.items()}}
         return out
 
     def unit_spread(rec, steps):

@@ -195,6 +195,38 @@ int slimattn_dag_build_1f1b(const slimattn_slice* slices, int32_t n_slices, cons
                             int32_t* n_vertices, int32_t* edge_from, int32_t* edge_to, int32_t* edge_kind,
                             int32_t cap_edges, int32_t* n_edges);
 
+/* Memory footprint over a timeline (paper: Memory footprint simulation -- allocation and release events are
+ * simulated chronologically on the execution timeline).  Buffer b belongs to stage buf_stage[b], holds
+ * buf_bytes[b] >= 0 bytes and is live from start[buf_alloc_vertex[b]] up to, not including,
+ * finish[buf_free_vertex[b]] (at one instant releases come before allocations).  start, finish [n_vertices] as
+ * slimattn_dag_timeline wrote them; stage_base [n_stages] the constant part of each stage (weights, optimizer
+ * states), NULL for zero.  peak_bytes, peak_time [n_stages] out: the largest live size of the stage and the
+ * earliest instant it is reached (0 if the stage has no live buffer).  All arrays HOST.
+ * ETABLE if a buffer would be released before it is allocated; EINVAL on bad indices or negative sizes. */
+int slimattn_dag_memory(int32_t n_vertices, const int64_t* start, const int64_t* finish, int32_t n_buffers,
+                        const int32_t* buf_stage, const int64_t* buf_bytes, const int32_t* buf_alloc_vertex,
+                        const int32_t* buf_free_vertex, int32_t n_stages, const int64_t* stage_base, int64_t* peak_bytes,
+                        int64_t* peak_time);
+
+/* The buffers of the graph slimattn_dag_build_1f1b makes of the same tables (same vertex ids), three per
+ * (stage, slice) in this order (paper: Memory footprint simulation -- activations held from the forward task to
+ * the corresponding backward task; KV cache and gradients managed per slice according to the schedule):
+ *   activations   act_bytes_per_token x q_len, from the slice's forward task to its backward task;
+ *   KV cache      kv_bytes_per_token x q_len, from the slice's forward task to the stage's last backward task
+ *                 that reads it: the last unit holding a slice of the same sample at or after it;
+ *   KV gradients  grad_bytes_per_token x q_len, from the first such backward task to the last (the rule of
+ *                 slimattn_bwd_released_rows at slice granularity).
+ * per_slice = 0 gives the sample-wise lifetimes to compare with: a sample's whole KV cache from its first
+ * forward task to its last backward task, its gradients from its first backward task to its last.
+ * buf_* [cap_buffers] out, *n_buffers = 3 * n_stages * n_slices.  All arrays HOST.  ECAP if cap_buffers is too
+ * small (n_buffers is still set); ETABLE on inconsistent lists; EINVAL on bad arguments. */
+int slimattn_dag_buffers_1f1b(const slimattn_slice* slices, int32_t n_slices, const int32_t* fwd_unit_ptr,
+                              const int32_t* fwd_unit_slices, int32_t n_fwd, const int32_t* bwd_unit_ptr,
+                              const int32_t* bwd_unit_slices, int32_t n_bwd, int32_t n_stages, int64_t act_bytes_per_token,
+                              int64_t kv_bytes_per_token, int64_t grad_bytes_per_token, int32_t per_slice, int32_t* buf_stage,
+                              int64_t* buf_bytes, int32_t* buf_alloc_vertex, int32_t* buf_free_vertex, int32_t cap_buffers,
+                              int32_t* n_buffers);
+
 /* Checks tables against the rules of the paper's PackFlow Pipeline Parallelism Scheduling section (slice order
  * within a sample preserved in the forward pass, backward first-in last-out) and of the MicroPack definition
  * (SlimPack System).  Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear

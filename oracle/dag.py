@@ -103,3 +103,62 @@ def build_1f1b(slices, fwd_units, bwd_units, n_stages: int, fwd_cost: Sequence[i
             order.append(B(s, j)); j += 1
         edges += [(a, b, EDGE_SCHEDULE) for a, b in zip(order, order[1:])]
     return vertices, weights, edges
+
+
+# ---- memory footprint over the timeline ---------------------------------------------------------------------
+
+def memory_peaks(start: Sequence[int], finish: Sequence[int], buffers, n_stages: int, base: Sequence[int]):
+    """Peak live bytes per stage, and the earliest time it is reached, straight from the definition.
+
+    Paper, Memory footprint simulation: with the execution timeline known, allocations and releases are events
+    in time, and the live size is followed chronologically.  A buffer (stage, bytes, alloc_vertex, free_vertex)
+    is live from Start(alloc_vertex) up to, not including, Finish(free_vertex): what is released at an instant
+    is gone before what is allocated at that instant arrives.  `base` is the stage's constant part (weights,
+    optimizer states).  The live size only rises at allocation instants, so those are the only candidates."""
+    peaks, times = [], []
+    for s in range(n_stages):
+        mine = [(int(by), start[a], finish[f]) for st, by, a, f in buffers if st == s]
+        for by, t0, t1 in mine:
+            if t1 < t0:
+                raise ValueError("a buffer is released before it is allocated")
+        best, at = 0, 0
+        for t in sorted({t0 for _, t0, _ in mine}):
+            live = sum(by for by, t0, t1 in mine if t0 <= t < t1)
+            if live > best:
+                best, at = live, t
+        peaks.append(int(base[s]) + best)
+        times.append(at)
+    return peaks, times
+
+
+def buffers_1f1b(slices, fwd_units, bwd_units, n_stages: int, act_bytes: int, kv_bytes: int, grad_bytes: int, per_slice: bool):
+    """Buffers of the 1F1B graph of `build_1f1b` (same vertex ids), three per (stage, slice), in that order:
+
+    activations   act_bytes per token of the slice: from the slice's forward task to its backward task
+                  (Memory footprint simulation: held until consumption by the corresponding backward task);
+    KV cache      kv_bytes per token: from the slice's forward task to the last backward task of the stage
+                  that needs it, i.e. the last unit with a slice of the same sample at or after it
+                  (KV cache managed per slice according to the schedule);
+    KV gradients  grad_bytes per token: from the first backward task that adds to them -- the first unit with a
+                  slice of the sample at or after it -- to the last one.
+    With per_slice False the KV cache and the gradients live sample-wise instead: the whole sample's cache
+    from the sample's first forward task to its last backward task, its gradients from its first backward task
+    to its last."""
+    (fp, fs), (bp, bs) = fwd_units, bwd_units
+    nf, nb = len(fp) - 1, len(bp) - 1
+    fwd_of = {int(t): u for u in range(nf) for t in fs[fp[u]:fp[u + 1]]}
+    bwd_of = {int(t): v for v in range(nb) for t in bs[bp[v]:bp[v + 1]]}
+    F = lambda s, u: s * nf + u
+    B = lambda s, v: n_stages * nf + s * nb + v
+    out = []
+    for s in range(n_stages):
+        for t, rec in enumerate(slices):
+            sample, idx, q_len = int(rec[0]), int(rec[1]), int(rec[3])
+            same = [x for x, r in enumerate(slices) if int(r[0]) == sample]
+            after = [x for x in same if int(slices[x][1]) >= idx] if per_slice else same
+            first_b, last_b = min(bwd_of[x] for x in after), max(bwd_of[x] for x in after)
+            kv_from = fwd_of[t] if per_slice else min(fwd_of[x] for x in same)
+            out.append((s, act_bytes * q_len, F(s, fwd_of[t]), B(s, bwd_of[t])))
+            out.append((s, kv_bytes * q_len, F(s, kv_from), B(s, last_b)))
+            out.append((s, grad_bytes * q_len, B(s, first_b), B(s, last_b)))
+    return out

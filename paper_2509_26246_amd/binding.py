@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create", "slimattn_tables_create_async",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_dag_memory", "slimattn_dag_buffers_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create", "slimattn_tables_create_async",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -72,6 +72,9 @@ def load_library():
     lib.slimattn_dag_timeline.argtypes = [C.c_int32, i64p, C.c_int32, i32p, i32p, i64p, i64p, i64p]
     lib.slimattn_dag_build_1f1b.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i64p, i64p,
                                             i32p, i64p, C.c_int32, i32p, i32p, i32p, i32p, C.c_int32, i32p]
+    lib.slimattn_dag_memory.argtypes = [C.c_int32, i64p, i64p, C.c_int32, i32p, i64p, i32p, i32p, C.c_int32, i64p, i64p, i64p]
+    lib.slimattn_dag_buffers_1f1b.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int64,
+                                              C.c_int64, C.c_int64, C.c_int32, i32p, i64p, i32p, i32p, C.c_int32, i32p]
     lib.slimattn_shape_supported.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.slimattn_slice_pairs.argtypes = [vp]
     lib.slimattn_slice_pairs.restype = C.c_int64
@@ -254,6 +257,39 @@ def dag_build_1f1b(slices, fwd_units, bwd_units, n_stages: int, fwd_cost, bwd_co
     n, m = nv.value, ne.value
     return {"vertex": vertex[:n].copy(), "weight": weight[:n].copy(), "edge_from": ef[:m].copy(), "edge_to": et[:m].copy(),
             "edge_kind": ek[:m].copy()}
+
+
+def dag_buffers_1f1b(slices, fwd_units, bwd_units, n_stages: int, act_bytes: int, kv_bytes: int, grad_bytes: int, per_slice: bool = True):
+    """slimattn_dag_buffers_1f1b -> dict(stage, bytes, alloc_vertex, free_vertex), three buffers per (stage, slice)."""
+    lib = load_library()
+    sl = _i32(slices).reshape(-1, 8)
+    fp, fs, bp, bs = _i32(fwd_units[0]), _i32(fwd_units[1]), _i32(bwd_units[0]), _i32(bwd_units[1])
+    n = 3 * n_stages * len(sl)
+    stage, alloc, free = (np.zeros(max(n, 1), np.int32) for _ in range(3))
+    size = np.zeros(max(n, 1), np.int64)
+    nb = C.c_int32(0)
+    rc = lib.slimattn_dag_buffers_1f1b(sl.ctypes.data, len(sl), _p(fp), _p(fs), len(fp) - 1, _p(bp), _p(bs), len(bp) - 1, n_stages,
+                                       act_bytes, kv_bytes, grad_bytes, int(per_slice), _p(stage), _p64(size), _p(alloc), _p(free), n,
+                                       C.byref(nb))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_dag_buffers_1f1b")
+    n = nb.value
+    return {"stage": stage[:n].copy(), "bytes": size[:n].copy(), "alloc_vertex": alloc[:n].copy(), "free_vertex": free[:n].copy()}
+
+
+def dag_memory(start, finish, buffers, n_stages: int, stage_base=None):
+    """slimattn_dag_memory -> (peak_bytes [n_stages], peak_time [n_stages]); `buffers` as dag_buffers_1f1b returns them."""
+    lib = load_library()
+    st, fi = _i64(start), _i64(finish)
+    stage, alloc, free = _i32(buffers["stage"]), _i32(buffers["alloc_vertex"]), _i32(buffers["free_vertex"])
+    size = _i64(buffers["bytes"])
+    base = _i64(stage_base) if stage_base is not None else None
+    peak, when = np.zeros(max(n_stages, 1), np.int64), np.zeros(max(n_stages, 1), np.int64)
+    rc = lib.slimattn_dag_memory(len(st), _p64(st), _p64(fi), len(stage), _p(stage), _p64(size), _p(alloc), _p(free), n_stages,
+                                 _p64(base) if base is not None else None, _p64(peak), _p64(when))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_dag_memory")
+    return peak[:n_stages].copy(), when[:n_stages].copy()
 
 
 def validate(cu, slices, unit_ptr, unit_slices, mode: int = CHECK_FORWARD) -> Tuple[int, str]:

@@ -16,9 +16,14 @@
 // samples have been issued on that stage (the paper's rule that a sample's backward starts after all of its
 // slices' forward passes); while the next backward unit is not ready the stage issues another forward unit
 // (PackFlow section: an extra forward MicroPack is injected).
+//
+// The same timeline carries the memory footprint (Memory footprint simulation): allocation and release events at
+// task starts and finishes, walked chronologically per stage; the 1F1B generator's buffers are each slice's
+// activations, KV cache and KV gradients.
 #include "internal.h"
 
 #include <algorithm>
+#include <climits>
 #include <vector>
 
 extern "C" {
@@ -165,6 +170,108 @@ int slimattn_dag_build_1f1b(const slimattn_slice* slices, int32_t n_slices, cons
     }
   }
   for (size_t e = 0; e < ef.size(); ++e) { edge_from[e] = ef[e]; edge_to[e] = et[e]; edge_kind[e] = ek[e]; }
+  return SLIMATTN_OK;
+}
+
+// Memory footprint over a timeline (paper: Memory footprint simulation).  Every buffer is an allocation event at
+// the start of one task and a release event at the finish of another; the events of a stage are walked in time
+// order, releases before allocations at equal instants, and the largest running sum is the stage's peak.
+int slimattn_dag_memory(int32_t n_vertices, const int64_t* start, const int64_t* finish, int32_t n_buffers,
+                        const int32_t* buf_stage, const int64_t* buf_bytes, const int32_t* buf_alloc_vertex,
+                        const int32_t* buf_free_vertex, int32_t n_stages, const int64_t* stage_base, int64_t* peak_bytes,
+                        int64_t* peak_time) {
+  if (n_vertices < 0 || n_buffers < 0 || n_stages < 0 || (n_vertices > 0 && (!start || !finish)) ||
+      (n_buffers > 0 && (!buf_stage || !buf_bytes || !buf_alloc_vertex || !buf_free_vertex)) || (n_stages > 0 && (!peak_bytes || !peak_time)))
+    return SLIMATTN_EINVAL;
+  struct Event { int64_t time; int32_t kind; int64_t bytes; };     // kind 0 = release, 1 = allocation
+  std::vector<std::vector<Event>> events(n_stages);
+  for (int32_t b = 0; b < n_buffers; ++b) {
+    const int32_t a = buf_alloc_vertex[b], f = buf_free_vertex[b];
+    if (buf_stage[b] < 0 || buf_stage[b] >= n_stages || a < 0 || a >= n_vertices || f < 0 || f >= n_vertices || buf_bytes[b] < 0) return SLIMATTN_EINVAL;
+    if (finish[f] < start[a]) return SLIMATTN_ETABLE;               // released before it exists
+    if (finish[f] == start[a]) continue;                            // never live
+    events[buf_stage[b]].push_back({start[a], 1, buf_bytes[b]});
+    events[buf_stage[b]].push_back({finish[f], 0, buf_bytes[b]});
+  }
+  for (int32_t s = 0; s < n_stages; ++s) {
+    auto& ev = events[s];
+    std::sort(ev.begin(), ev.end(), [](const Event& x, const Event& y) { return x.time != y.time ? x.time < y.time : x.kind < y.kind; });
+    int64_t live = 0, best = 0, at = 0;
+    for (size_t i = 0; i < ev.size(); ++i) {
+      live += ev[i].kind ? ev[i].bytes : -ev[i].bytes;
+      // the sum counts once all events of an instant are in
+      if ((i + 1 == ev.size() || ev[i + 1].time != ev[i].time) && live > best) { best = live; at = ev[i].time; }
+    }
+    peak_bytes[s] = (stage_base ? stage_base[s] : 0) + best;
+    peak_time[s] = at;
+  }
+  return SLIMATTN_OK;
+}
+
+int slimattn_dag_buffers_1f1b(const slimattn_slice* slices, int32_t n_slices, const int32_t* fwd_unit_ptr,
+                              const int32_t* fwd_unit_slices, int32_t n_fwd, const int32_t* bwd_unit_ptr,
+                              const int32_t* bwd_unit_slices, int32_t n_bwd, int32_t n_stages, int64_t act_bytes_per_token,
+                              int64_t kv_bytes_per_token, int64_t grad_bytes_per_token, int32_t per_slice, int32_t* buf_stage,
+                              int64_t* buf_bytes, int32_t* buf_alloc_vertex, int32_t* buf_free_vertex, int32_t cap_buffers,
+                              int32_t* n_buffers) {
+  if (n_slices < 0 || n_fwd < 0 || n_bwd < 0 || n_stages < 1 || !fwd_unit_ptr || !bwd_unit_ptr || !n_buffers ||
+      (n_slices > 0 && (!slices || !fwd_unit_slices || !bwd_unit_slices)) || act_bytes_per_token < 0 || kv_bytes_per_token < 0 ||
+      grad_bytes_per_token < 0)
+    return SLIMATTN_EINVAL;
+  if (fwd_unit_ptr[n_fwd] != n_slices || bwd_unit_ptr[n_bwd] != n_slices) return SLIMATTN_ETABLE;
+  std::vector<int32_t> fwd_of(n_slices, -1), bwd_of(n_slices, -1);
+  for (int32_t u = 0; u < n_fwd; ++u)
+    for (int32_t i = fwd_unit_ptr[u]; i < fwd_unit_ptr[u + 1]; ++i) {
+      if (fwd_unit_slices[i] < 0 || fwd_unit_slices[i] >= n_slices || fwd_of[fwd_unit_slices[i]] != -1) return SLIMATTN_ETABLE;
+      fwd_of[fwd_unit_slices[i]] = u;
+    }
+  for (int32_t v = 0; v < n_bwd; ++v)
+    for (int32_t i = bwd_unit_ptr[v]; i < bwd_unit_ptr[v + 1]; ++i) {
+      if (bwd_unit_slices[i] < 0 || bwd_unit_slices[i] >= n_slices || bwd_of[bwd_unit_slices[i]] != -1) return SLIMATTN_ETABLE;
+      bwd_of[bwd_unit_slices[i]] = v;
+    }
+  int32_t n_samples = 0;
+  for (int32_t t = 0; t < n_slices; ++t) {
+    if (slices[t].sample < 0 || slices[t].idx_in_sample < 0) return SLIMATTN_ETABLE;
+    n_samples = std::max(n_samples, slices[t].sample + 1);
+  }
+  const int64_t total = (int64_t)3 * n_stages * n_slices;
+  *n_buffers = (int32_t)total;
+  if (total > cap_buffers) return SLIMATTN_ECAP;
+  if (total > 0 && (!buf_stage || !buf_bytes || !buf_alloc_vertex || !buf_free_vertex)) return SLIMATTN_EINVAL;
+  // per slice: the first and the last backward unit among the sample's slices at or after it (a sample's slices
+  // walked from its last to its first, carrying the running minimum and maximum); per sample: over all slices
+  std::vector<std::vector<int32_t>> of_sample(n_samples);
+  for (int32_t t = 0; t < n_slices; ++t) of_sample[slices[t].sample].push_back(t);
+  std::vector<int32_t> first_b(n_slices), last_b(n_slices), kv_from(n_slices);
+  for (auto& ts : of_sample) {
+    std::sort(ts.begin(), ts.end(), [&](int32_t a, int32_t b) { return slices[a].idx_in_sample < slices[b].idx_in_sample; });
+    int32_t lo = INT32_MAX, hi = -1, f_lo = INT32_MAX;
+    for (size_t i = ts.size(); i-- > 0;) {
+      lo = std::min(lo, bwd_of[ts[i]]);
+      hi = std::max(hi, bwd_of[ts[i]]);
+      f_lo = std::min(f_lo, fwd_of[ts[i]]);
+      first_b[ts[i]] = lo;
+      last_b[ts[i]] = hi;
+      kv_from[ts[i]] = fwd_of[ts[i]];
+    }
+    if (!per_slice)
+      for (int32_t t : ts) { first_b[t] = lo; last_b[t] = hi; kv_from[t] = f_lo; }
+  }
+  auto F = [&](int32_t s, int32_t u) { return s * n_fwd + u; };
+  auto B = [&](int32_t s, int32_t v) { return n_stages * n_fwd + s * n_bwd + v; };
+  int64_t b = 0;
+  auto put = [&](int32_t s, int64_t bytes, int32_t from, int32_t to) {
+    buf_stage[b] = s; buf_bytes[b] = bytes; buf_alloc_vertex[b] = from; buf_free_vertex[b] = to;
+    ++b;
+  };
+  for (int32_t s = 0; s < n_stages; ++s)
+    for (int32_t t = 0; t < n_slices; ++t) {
+      const int64_t n = slices[t].q_len;
+      put(s, act_bytes_per_token * n, F(s, fwd_of[t]), B(s, bwd_of[t]));
+      put(s, kv_bytes_per_token * n, F(s, kv_from[t]), B(s, last_b[t]));
+      put(s, grad_bytes_per_token * n, B(s, first_b[t]), B(s, last_b[t]));
+    }
   return SLIMATTN_OK;
 }
 

@@ -134,3 +134,97 @@ def test_native_graph_builder_bit_exact_and_asymmetric_lists_resolve():
                 for t in bwd[1][bwd[0][v]:bwd[0][v + 1]]:
                     for s in range(p):
                         assert start[p * nf + s * nb + v] >= finish[s * nf + fwd_of[int(t)]]
+
+
+# ---- memory footprint ---------------------------------------------------------------------------------------
+
+def _csr(units):
+    ptr = np.cumsum([0] + [len(u) for u in units]).astype(np.int32)
+    return ptr, np.array([t for u in units for t in u], np.int32)
+
+
+def test_memory_footprint_of_the_hand_worked_schedule():
+    import json
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "dag_memory_tiny.json")))
+    cu, sl = T.build_slices(g["lengths"], g["slice_size"])
+    fwd, bwd = _csr(g["fwd_units"]), _csr(g["bwd_units"])
+    p = g["n_stages"]
+    vertices, weights, edges = D.build_1f1b(sl, fwd, bwd, p, g["fwd_cost"], g["bwd_cost"])
+    start, finish, total = D.timeline(weights, [(u, v) for u, v, _ in edges])
+    assert start[:4] == g["start_fwd"] and start[4:] == g["start_bwd"] and total == g["total"]
+    for c in g["cases"]:
+        bufs = D.buffers_1f1b(sl, fwd, bwd, p, c["act"], c["kv"], c["grad"], c["per_slice"])
+        assert D.memory_peaks(start, finish, bufs, p, [0]) == ([c["peak"]], [c["at"]])
+        assert D.memory_peaks(start, finish, bufs, p, [1000]) == ([1000 + c["peak"]], [c["at"]])      # weights on top
+        nb = S.dag_buffers_1f1b(sl, fwd, bwd, p, c["act"], c["kv"], c["grad"], c["per_slice"])
+        assert list(zip(nb["stage"].tolist(), nb["bytes"].tolist(), nb["alloc_vertex"].tolist(), nb["free_vertex"].tolist())) == bufs
+        peak, when = S.dag_memory(start, finish, nb, p)
+        assert (peak.tolist(), when.tolist()) == ([c["peak"]], [c["at"]])
+
+
+@pytest.mark.parametrize("p,m,f,b", [(1, 3, 2, 5), (2, 2, 1, 2), (4, 4, 3, 6), (4, 9, 2, 5), (8, 16, 10, 25), (5, 3, 4, 4)])
+def test_uniform_1f1b_keeps_p_minus_s_micro_batches_of_activations(p, m, f, b):
+    # the textbook property of 1F1B: stage s holds the activations of at most min(m, p - s) micro-batches, and
+    # reaches that; a release and an allocation at the same instant do not add up
+    sl, units = _whole_sample_tables(m)                 # 8 tokens per micro-batch
+    vertices, weights, edges = D.build_1f1b(sl, units, units, p, [f] * m, [b] * m)
+    start, finish, _ = D.timeline(weights, [(u, v) for u, v, _ in edges])
+    bufs = D.buffers_1f1b(sl, units, units, p, 7, 0, 0, True)
+    peaks, _ = D.memory_peaks(start, finish, bufs, p, [0] * p)
+    assert peaks == [7 * 8 * min(m, p - s) for s in range(p)]
+    peak, _ = S.dag_memory(start, finish, S.dag_buffers_1f1b(sl, units, units, p, 7, 0, 0, True), p)
+    assert peak.tolist() == peaks
+
+
+def test_memory_peaks_against_a_scan_of_every_instant_and_the_native_sweep():
+    r = np.random.default_rng(12)
+    for _ in range(40):
+        n_v, n_b, p = int(r.integers(1, 10)), int(r.integers(0, 14)), int(r.integers(1, 4))
+        start = [int(x) for x in r.integers(0, 12, n_v)]
+        finish = [s + int(x) for s, x in zip(start, r.integers(0, 6, n_v))]
+        bufs = []
+        for _ in range(n_b):
+            a, f = int(r.integers(n_v)), int(r.integers(n_v))
+            if finish[f] < start[a]:
+                a, f = f, a                              # start[f] <= finish[f] < start[a] <= finish[a]
+            bufs.append((int(r.integers(p)), int(r.integers(0, 50)), a, f))
+        base = [int(x) for x in r.integers(0, 9, p)]
+        peaks, times = D.memory_peaks(start, finish, bufs, p, base)
+        # every integer instant of the timeline, half-open lifetimes
+        for s in range(p):
+            live = [sum(by for st, by, a, f in bufs if st == s and start[a] <= t < finish[f]) for t in range(0, 20)]
+            assert peaks[s] == base[s] + max(live) and (max(live) == 0 or live.index(max(live)) == times[s])
+        d = {"stage": [b[0] for b in bufs], "bytes": [b[1] for b in bufs], "alloc_vertex": [b[2] for b in bufs], "free_vertex": [b[3] for b in bufs]}
+        peak, when = S.dag_memory(start, finish, d, p, base)
+        assert peak.tolist() == peaks and when.tolist() == times
+    with pytest.raises(ValueError):
+        D.memory_peaks([5, 0], [6, 1], [(0, 1, 0, 1)], 1, [0])
+    with pytest.raises(S.SlimAttnError) as e:
+        S.dag_memory([5, 0], [6, 1], {"stage": [0], "bytes": [1], "alloc_vertex": [0], "free_vertex": [1]}, 1)
+    assert e.value.code == -2
+
+
+def test_native_buffers_bit_exact_and_per_slice_lifetimes_never_cost_more():
+    r = np.random.default_rng(21)
+    for _ in range(25):
+        lengths = r.integers(1, 90, size=r.integers(1, 7)).tolist()
+        cu, sl = T.build_slices(lengths, int(r.integers(4, 40)))
+        fwd = T.build_units(cu, sl, "PREFIX_FILL", m=int(r.integers(1, 7)), w_quad=2, w_lin=0, backward=False)
+        bwd = T.build_units(cu, sl, "PREFIX_FILL", m=int(r.integers(1, 9)), w_quad=5, w_lin=0, backward=True)
+        nf, nb = len(fwd[0]) - 1, len(bwd[0]) - 1
+        fc, bc = [int(x) for x in r.integers(1, 50, nf)], [int(x) for x in r.integers(1, 120, nb)]
+        for p in (1, 3):
+            vertices, weights, edges = D.build_1f1b(sl, fwd, bwd, p, fc, bc)
+            start, finish, _ = D.timeline(weights, [(u, v) for u, v, _ in edges])
+            act, kv, grad = (int(x) for x in r.integers(0, 9, 3))
+            peaks = {}
+            for per_slice in (True, False):
+                bufs = D.buffers_1f1b(sl, fwd, bwd, p, act, kv, grad, per_slice)
+                nbuf = S.dag_buffers_1f1b(sl, fwd, bwd, p, act, kv, grad, per_slice)
+                assert list(zip(nbuf["stage"].tolist(), nbuf["bytes"].tolist(), nbuf["alloc_vertex"].tolist(), nbuf["free_vertex"].tolist())) == bufs
+                peaks[per_slice], times = D.memory_peaks(start, finish, bufs, p, [0] * p)
+                got, when = S.dag_memory(start, finish, nbuf, p)
+                assert got.tolist() == peaks[per_slice] and when.tolist() == times
+            # a per-slice lifetime lies inside the sample-wise one, buffer by buffer
+            assert all(a <= b for a, b in zip(peaks[True], peaks[False]))
