@@ -14,6 +14,7 @@ with the spread of per-unit times.  `--per-unit` makes that mode the main measur
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import statistics
@@ -222,21 +223,32 @@ def main():
         """Runs warmup + steps over the packs `which` (default: all, cycling); returns wall seconds, pairs done and
         the per-launch records (class, pass, unit, ms)."""
         idx = list(range(n_packs)) if which is None else list(which)
+        # The warm-up runs timed like the steps and nothing but a synchronisation separates the two; its records are
+        # cut off afterwards.  The interpreter's cyclic garbage collector stays off meanwhile: a full collection
+        # (tens of milliseconds with torch loaded) inside the first calls of the timed loop, when the GPU has
+        # little queued, left the GPU idle for as long.
+        gc.collect()
+        gc.disable()
+        n_warm = sum(launches_per_step(probs[idx[i % len(idx)]]) for i in range(warmup))
+        S.profile_enable(n_warm + sum(launches_per_step(probs[idx[i % len(idx)]]) for i in range(steps)) + 16)
         for i in range(warmup):
             p = probs[idx[i % len(idx)]]
             p.forward(flags=flags); p.backward(flags=flags)
-        torch.cuda.synchronize()
-        S.profile_enable(sum(launches_per_step(probs[idx[i % len(idx)]]) for i in range(steps)) + 16)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
             p = probs[idx[i % len(idx)]]
             p.forward(flags=flags); p.backward(flags=flags)
+        measure.host_enqueue_s = time.perf_counter() - t0    # all launches queued; the GPU is still working
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        rec = S.profile_read_launches()
+        gc.enable()
+        cls, ps, un, ms = S.profile_read_launches()
         S.profile_enable(0)
-        return t1 - t0, sum(pairs[idx[i % len(idx)]] for i in range(steps)), rec
+        # the warm-up's records: everything before the record of the (warmup + 1)-th forward call (a call's own
+        # record precedes those of its kernels)
+        first = int(np.flatnonzero(cls == S.KERNEL_CLASSES.index("fwd_call"))[warmup]) if warmup > 0 else 0
+        return t1 - t0, sum(pairs[idx[i % len(idx)]] for i in range(steps)), (cls[first:], ps[first:], un[first:], ms[first:])
 
     def summarise(wall, tot_pairs, rec, steps):
         cls, ps, un, ms = rec
@@ -314,6 +326,7 @@ def main():
     main_flags = S.FLAG_PER_UNIT_LAUNCH if args.per_unit else 0
     wall, tot_pairs, rec = measure(main_flags, args.steps, args.warmup)
     main_sum, per = summarise(wall, tot_pairs, rec, args.steps)
+    host_enqueue_ms = measure.host_enqueue_s * 1e3 / max(args.steps, 1)
 
     # Per kernel: algorithmic and executed throughput, algorithmic HBM rate.  Executed pairs and bytes are those
     # of the scopes the main measurement launched.
@@ -383,7 +396,8 @@ def main():
                    "fwd_units": [p.tables.n_fwd_units for p in probs], "bwd_units": [p.tables.n_bwd_units for p in probs]},
         "fwd_tflops": main_sum["fwd_tflops"], "bwd_tflops": main_sum["bwd_tflops"],
         "fwd_pct_bf16_peak": main_sum["fwd_pct_bf16_peak"], "bwd_pct_bf16_peak": main_sum["bwd_pct_bf16_peak"],
-        "kernel_ms_per_step": main_sum["kernel_ms_per_step"], "call_ms_per_step": main_sum["call_ms_per_step"], "kernels": kernels,
+        "kernel_ms_per_step": main_sum["kernel_ms_per_step"], "call_ms_per_step": main_sum["call_ms_per_step"],
+        "host_enqueue_ms_per_step": host_enqueue_ms, "kernels": kernels,
         "table_build_ms": {k_: statistics.median(v_) for k_, v_ in build_ms.items()},
         "roofline": roofline,
     }
