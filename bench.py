@@ -250,6 +250,26 @@ def main():
         first = int(np.flatnonzero(cls == S.KERNEL_CLASSES.index("fwd_call"))[warmup]) if warmup > 0 else 0
         return t1 - t0, sum(pairs[idx[i % len(idx)]] for i in range(steps)), (cls[first:], ps[first:], un[first:], ms[first:])
 
+    def measure_graph(flags, steps, warmup):
+        """The same step replayed from a HIP graph per pack (forward + backward recorded once by stream capture):
+        what is left of the gaps between a step's launches when the host does not issue them one by one.  No
+        per-kernel events (they are not part of a capture): wall time only."""
+        graphs = [p.capture_step(flags) for p in probs]
+        gc.collect()
+        gc.disable()
+        for i in range(warmup):
+            graphs[i % n_packs].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % n_packs].replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        gc.enable()
+        tot = sum(pairs[i % n_packs] for i in range(steps))
+        del graphs
+        return {"value": (S.flops_fwd(tot, d, hq) + S.flops_bwd(tot, d, hq)) / (t1 - t0) / 1e12, "ms_per_step": (t1 - t0) * 1e3 / max(steps, 1)}
+
     def summarise(wall, tot_pairs, rec, steps):
         cls, ps, un, ms = rec
         per = {c: (float(ms[cls == i].sum()), int((cls == i).sum())) for i, c in enumerate(S.KERNEL_CLASSES)}
@@ -404,6 +424,7 @@ def main():
     if args.per_unit:
         out["unit_ms"] = unit_spread(rec, args.steps)
         out["pipeline_1f1b"] = pipeline_sim(rec)
+        out["hip_graph_replay"] = measure_graph(main_flags, args.steps, min(args.warmup, 4))
 
     if not args.brief:
         # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
@@ -421,6 +442,7 @@ def main():
             s_, _ = summarise(wl, pr, rc, args.steps)
             s_["unit_ms"] = unit_spread(rc, args.steps)
             s_["pipeline_1f1b"] = pipeline_sim(rc)
+            s_["hip_graph_replay"] = measure_graph(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
             out["per_unit"] = s_
             if args.partition == "policy":
                 # the same packs partitioned by the exact solver instead of the greedy policies (same unit counts):
@@ -435,6 +457,7 @@ def main():
                 s2, _ = summarise(wl, pr, rc, args.steps)
                 s2["unit_ms"] = unit_spread(rc, args.steps)
                 s2["pipeline_1f1b"] = pipeline_sim(rc)
+                s2["hip_graph_replay"] = measure_graph(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
                 s2["fwd_units"] = [p_.tables.n_fwd_units for p_ in probs]
                 s2["bwd_units"] = [p_.tables.n_bwd_units for p_ in probs]
                 s2["slices"] = [len(t_[1]) for t_ in tabs]

@@ -62,6 +62,24 @@ class Problem:
         B.bwd(self.q, self.k, self.v, self.o, self.lse, self.dO, self.tables, self.dQ, self.dK, self.dV,
               self.workspace, **self._kw(**over))
 
+    def capture_step(self, flags: int = 0) -> "torch.cuda.CUDAGraph":
+        """Forward + backward of the pack recorded into a HIP graph.  The two calls only launch kernels on the
+        stream they are given (no allocation, no synchronisation, no memset), so a stream capture takes them as
+        they are; per-kernel timing must be off (its events are not part of a capture).  Replaying the graph
+        re-runs every launch on the same buffers."""
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # once outside the capture: first-call set-up is not recorded
+            self.forward(flags=flags)
+            self.backward(flags=flags)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            self.forward(flags=flags)
+            self.backward(flags=flags)
+        return g
+
 
 def make_problem(q: np.ndarray, k: np.ndarray, v: np.ndarray, dO: np.ndarray, cu, slices, fwd_units, bwd_units, *,
                  bf16: bool, scale: Optional[float] = None, device="cuda:0") -> Problem:
