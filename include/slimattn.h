@@ -295,7 +295,9 @@ int slimattn_shape_supported(int64_t total_tokens, int32_t max_sample_len, int32
  * K/V need not exist yet), and o/lse rows of slices outside the range are not written.  A runtime can
  * therefore call it one unit at a time as K/V arrive slice by slice.
  * q, k, v DEVICE (read), o, lse DEVICE (written), 16-byte aligned.
- * stream: a hipStream_t (NULL = default stream).  Allocates nothing, does not synchronise. */
+ * stream: a hipStream_t (NULL = default stream).  Allocates nothing, does not synchronise, issues kernel
+ * launches only (no memset, no copy): the call -- and slimattn_bwd likewise -- may be recorded by a stream
+ * capture into a HIP graph, with slimattn_profile_enable off (its events do not belong in a capture). */
 int slimattn_fwd(const slimattn_params* p, const void* q, const void* k, const void* v,
                  const slimattn_tables* t, void* o, float* lse, void* stream);
 
