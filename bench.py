@@ -430,8 +430,8 @@ def main():
         # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
         per_seed = {}
         for i, seed in enumerate(seeds):
-            wl, pr, rc = measure(main_flags, 6, 2, which=[i])
-            s_, _ = summarise(wl, pr, rc, 6)
+            wl, pr, rc = measure(main_flags, 12, 4, which=[i])
+            s_, _ = summarise(wl, pr, rc, 12)
             per_seed[str(seed)] = {"value": s_["value"], "fwd_tflops": s_["fwd_tflops"], "bwd_tflops": s_["bwd_tflops"],
                                    "pairs": pairs[i], "samples": int(len(packs[i][0])), "longest": int(packs[i][0].max())}
         out["per_seed"] = per_seed
