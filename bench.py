@@ -326,6 +326,43 @@ def main():
                                 "peak_mib_worst_stage": {k_: round(v_ / n_packs, 1) for k_, v_ in mem.items()}}
         return out
 
+    def unit_count_search(rec, stages=4, m_max=64):
+        """The paper's outer loop on this GPU's own timings: task time = fixed + cost x rate per pass, fitted by least
+        squares to the measured per-unit times of `rec` (cost = the workload's weights on pairs and rows); then, per
+        pack, every candidate unit count (multiples of the pipeline width on the logarithmic grid) is partitioned by the
+        exact solver, priced, and run through the 1F1B simulator with its memory footprint.  Mean over the packs."""
+        ut = unit_times(rec)
+        wts = {0: (w.fwd_policy[1].get("w_quad", 2), w.fwd_policy[1].get("w_lin", 0)),
+               1: (w.bwd_policy[1].get("w_quad", 5), w.bwd_policy[1].get("w_lin", 0))}
+        rates = {}
+        for pss in (0, 1):
+            xs, ys = [], []
+            for i, (cu, sl, fu, bu) in enumerate(tabs):
+                ptr, flat = (fu, bu)[pss]
+                for u in range(len(ptr) - 1):
+                    cost = sum(wts[pss][0] * S.slice_pairs(sl[t]) + wts[pss][1] * int(sl[t][3]) for t in flat[ptr[u]:ptr[u + 1]])
+                    xs.append(float(cost)); ys.append(ut[(pss, i, u)] * 1e6)             # ns
+            slope, icpt = np.polyfit(np.array(xs), np.array(ys), 1) if len(xs) > 1 else (ys[0] / max(xs[0], 1.0), 0.0)
+            rates[pss] = (max(0, int(round(icpt))), max(1, int(round(slope * 2 ** 30))), 2 ** 30)
+        cands = S.candidate_unit_counts(stages, m_max)
+        granule = args.granule or max(256, 256 * 128 // max(1, w.n_q_heads // 2))
+        solver = dict(w_quad_fwd=wts[0][0], w_lin_fwd=wts[0][1], w_quad_bwd=wts[1][0], w_lin_bwd=wts[1][1], granule=granule,
+                      max_slice=max(w.slice_size, granule))
+        kv_b, grad_b, act_b = 2 * hkv * d * 2, 2 * hkv * d * 4, 2 * hq * d * 2 + hq * 4
+        t_sum, pk_sum, chosen = np.zeros(len(cands)), np.zeros(len(cands)), []
+        t0 = time.perf_counter()
+        for L, *_ in packs:
+            t, pk, best = S.search_unit_count(L, cands, solver, stages, rates[0], rates[1], act_b, kv_b, grad_b, n_threads=8)
+            t_sum += t * 1e-6
+            pk_sum += pk / 2 ** 20
+            chosen.append(int(cands[best]) if best >= 0 else -1)
+        search_ms = (time.perf_counter() - t0) * 1e3 / n_packs
+        return {"stages": stages, "fit_ns": {"fwd_fixed_ns": rates[0][0], "fwd_ns_per_1e9_cost": rates[0][1] / 2 ** 30 * 1e9,
+                                             "bwd_fixed_ns": rates[1][0], "bwd_ns_per_1e9_cost": rates[1][1] / 2 ** 30 * 1e9},
+                "candidates": [int(m) for m in cands], "predicted_ms": [round(x / n_packs, 3) for x in t_sum],
+                "peak_mib_worst_stage": [round(x / n_packs, 1) for x in pk_sum], "chosen_per_pack": chosen,
+                "search_ms_per_pack": round(search_ms, 3)}
+
     def unit_spread(rec, steps):
         """Time of each scheduling unit (all kernels launched for it, averaged over the steps in which its pack ran):
         spread over the units of all packs together, and the coefficient of variation inside each pack (the packs
@@ -425,6 +462,7 @@ def main():
         out["unit_ms"] = unit_spread(rec, args.steps)
         out["pipeline_1f1b"] = pipeline_sim(rec)
         out["hip_graph_replay"] = measure_graph(main_flags, args.steps, min(args.warmup, 4))
+        out["unit_count_search"] = unit_count_search(rec)
 
     if not args.brief:
         # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
@@ -443,6 +481,7 @@ def main():
             s_["unit_ms"] = unit_spread(rc, args.steps)
             s_["pipeline_1f1b"] = pipeline_sim(rc)
             s_["hip_graph_replay"] = measure_graph(S.FLAG_PER_UNIT_LAUNCH, args.steps, min(args.warmup, 4))
+            s_["unit_count_search"] = unit_count_search(rc)
             out["per_unit"] = s_
             if args.partition == "policy":
                 # the same packs partitioned by the exact solver instead of the greedy policies (same unit counts):

@@ -227,6 +227,41 @@ int slimattn_dag_buffers_1f1b(const slimattn_slice* slices, int32_t n_slices, co
                               int64_t* buf_bytes, int32_t* buf_alloc_vertex, int32_t* buf_free_vertex, int32_t cap_buffers,
                               int32_t* n_buffers);
 
+/* ---- search over the number of units (host only) ----------------------------------------------------- */
+
+/* How a candidate is priced (paper: Primitive Measurements and Search Space -- runtimes estimated from the
+ * theoretical cost with utilisations calibrated by preliminary benchmarks; DAG-based Pipeline Simulator).
+ * Task time of a unit = fixed + cost * num / den (integer division), cost = w_quad * pairs + w_lin * rows of
+ * its slices with the pass's weights of slimattn_solver; any time unit.  Bytes per token as in
+ * slimattn_dag_buffers_1f1b (per-slice lifetimes).  stage_bytes_cap > 0: a candidate whose worst stage's peak
+ * exceeds it is not chosen. */
+typedef struct slimattn_search {
+  int32_t n_stages;
+  int32_t pad0;
+  int64_t fwd_fixed, fwd_num, fwd_den;
+  int64_t bwd_fixed, bwd_num, bwd_den;
+  int64_t act_bytes_per_token, kv_bytes_per_token, grad_bytes_per_token;
+  int64_t stage_bytes_cap;
+} slimattn_search;
+
+/* Candidate unit counts m = i * n_stages <= m_max for i = 1, 2, 3, 4, 6, 8, 12, 16, 24, ... (paper: Primitive
+ * Measurements and Search Space -- m quantised to multiples of the pipeline width, i sampled on a roughly
+ * logarithmic grid; the grid itself is this build's: the powers of two and the values halfway between).
+ * out [cap] ascending, *n_out the count (ECAP if cap is too small; the count is still set).  HOST. */
+int slimattn_candidate_unit_counts(int32_t n_stages, int32_t m_max, int32_t* out, int32_t cap, int32_t* n_out);
+
+/* For each candidate m_list[i] (used as the unit count of both passes; m_fwd / m_bwd of `sp` are ignored):
+ * the exact partition (slimattn_solve_partition), its units priced by `ss`, through the 1F1B graph of
+ * ss->n_stages stages (slimattn_dag_build_1f1b, slimattn_dag_timeline) and the memory footprint
+ * (slimattn_dag_buffers_1f1b, slimattn_dag_memory): t_total[i] the simulated iteration time, peak_bytes[i]
+ * the worst stage's peak; both -1 where the token cap makes m_list[i] units infeasible.  *best = index of the
+ * candidate with the smallest t_total among those within stage_bytes_cap (ties: the earlier entry), -1 if
+ * none (paper: Balanced Packing & Asymmetric Partitioning Solver -- several MicroPack counts are evaluated
+ * and the best kept).  Candidates are evaluated by n_threads workers.  All arrays HOST [n_m]. */
+int slimattn_search_unit_count(const int32_t* lengths, int32_t n, const slimattn_solver* sp, const slimattn_search* ss,
+                               const int32_t* m_list, int32_t n_m, int32_t n_threads, int64_t* t_total, int64_t* peak_bytes,
+                               int32_t* best);
+
 /* Checks tables against the rules of the paper's PackFlow Pipeline Parallelism Scheduling section (slice order
  * within a sample preserved in the forward pass, backward first-in last-out) and of the MicroPack definition
  * (SlimPack System).  Structural rules (always): cu starts at 0 and is non-decreasing; the slices of a sample appear

@@ -7,7 +7,7 @@ imports it, and it imports nothing from the product path.
 
 Modules: attention.py (fp64 causal attention over packed samples, forward and backward, by definition and
 table-driven), tables.py (slice table, unit lists, cost model, validation), solver.py (exact min-max partition
-by dynamic programming), dag.py (execution timeline of a task graph, 1F1B graph over asymmetric unit lists, memory footprint over the timeline).
+by dynamic programming), dag.py (execution timeline of a task graph, 1F1B graph over asymmetric unit lists, memory footprint over the timeline), search.py (the candidate unit counts and the choice among them, composed of the three above).
 
 Parity pins (all in tests/, CPU-only): library cross-check against PyTorch's
 fp64 scaled-dot-product attention with autograd, central finite differences,

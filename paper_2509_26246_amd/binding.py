@@ -18,7 +18,7 @@ POLICY_KINDS = {"ALL": 0, "PER_SAMPLE": 1, "ROUND_ROBIN": 2, "PREFIX_FILL": 3, "
                 "ISOLATE_FILL": 6}
 EXPORTED_SYMBOLS = [
     "slimattn_build_slices", "slimattn_build_slices_from_bounds", "slimattn_build_units", "slimattn_validate",
-    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_dag_memory", "slimattn_dag_buffers_1f1b", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create", "slimattn_tables_create_async",
+    "slimattn_solve_partition", "slimattn_solve_bottlenecks", "slimattn_dag_timeline", "slimattn_dag_build_1f1b", "slimattn_dag_memory", "slimattn_dag_buffers_1f1b", "slimattn_candidate_unit_counts", "slimattn_search_unit_count", "slimattn_shape_supported", "slimattn_slice_pairs", "slimattn_flops_fwd", "slimattn_flops_bwd", "slimattn_tables_create", "slimattn_tables_create_async",
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
@@ -75,6 +75,9 @@ def load_library():
     lib.slimattn_dag_memory.argtypes = [C.c_int32, i64p, i64p, C.c_int32, i32p, i64p, i32p, i32p, C.c_int32, i64p, i64p, i64p]
     lib.slimattn_dag_buffers_1f1b.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, C.c_int64,
                                               C.c_int64, C.c_int64, C.c_int32, i32p, i64p, i32p, i32p, C.c_int32, i32p]
+    lib.slimattn_candidate_unit_counts.argtypes = [C.c_int32, C.c_int32, i32p, C.c_int32, i32p]
+    lib.slimattn_search_unit_count.argtypes = [i32p, C.c_int32, C.POINTER(_Solver), C.POINTER(_Search), i32p, C.c_int32, C.c_int32,
+                                               i64p, i64p, i32p]
     lib.slimattn_shape_supported.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.slimattn_slice_pairs.argtypes = [vp]
     lib.slimattn_slice_pairs.restype = C.c_int64
@@ -257,6 +260,45 @@ def dag_build_1f1b(slices, fwd_units, bwd_units, n_stages: int, fwd_cost, bwd_co
     n, m = nv.value, ne.value
     return {"vertex": vertex[:n].copy(), "weight": weight[:n].copy(), "edge_from": ef[:m].copy(), "edge_to": et[:m].copy(),
             "edge_kind": ek[:m].copy()}
+
+
+class _Search(C.Structure):
+    _fields_ = [("n_stages", C.c_int32), ("pad0", C.c_int32), ("fwd_fixed", C.c_int64), ("fwd_num", C.c_int64), ("fwd_den", C.c_int64),
+                ("bwd_fixed", C.c_int64), ("bwd_num", C.c_int64), ("bwd_den", C.c_int64), ("act_bytes_per_token", C.c_int64),
+                ("kv_bytes_per_token", C.c_int64), ("grad_bytes_per_token", C.c_int64), ("stage_bytes_cap", C.c_int64)]
+
+
+def candidate_unit_counts(n_stages: int, m_max: int) -> np.ndarray:
+    """slimattn_candidate_unit_counts -> ascending candidate unit counts (multiples of n_stages up to m_max)."""
+    lib = load_library()
+    n = C.c_int32(0)
+    rc = lib.slimattn_candidate_unit_counts(n_stages, m_max, None, 0, C.byref(n))
+    if rc not in (0, -3):
+        raise SlimAttnError(rc, "slimattn_candidate_unit_counts")
+    out = np.zeros(max(n.value, 1), np.int32)
+    rc = lib.slimattn_candidate_unit_counts(n_stages, m_max, _p(out), n.value, C.byref(n))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_candidate_unit_counts")
+    return out[:n.value].copy()
+
+
+def search_unit_count(lengths: Sequence[int], m_list: Sequence[int], solver: dict, n_stages: int, fwd_rate, bwd_rate, act_bytes: int = 0,
+                      kv_bytes: int = 0, grad_bytes: int = 0, stage_bytes_cap: int = 0, n_threads: int = 4):
+    """slimattn_search_unit_count -> (t_total [n_m], peak_bytes [n_m], best index or -1).  solver: the keyword
+    parameters of solve_partition (m_fwd / m_bwd ignored); fwd_rate, bwd_rate = (fixed, num, den)."""
+    lib = load_library()
+    L, M = _i32(lengths), _i32(m_list)
+    params = dict(solver)
+    params.setdefault("m_fwd", 1)
+    params.setdefault("m_bwd", 1)
+    sp = _solver(**params)
+    ss = _Search(n_stages, 0, *[int(x) for x in fwd_rate], *[int(x) for x in bwd_rate], act_bytes, kv_bytes, grad_bytes, stage_bytes_cap)
+    t, pk = np.zeros(max(len(M), 1), np.int64), np.zeros(max(len(M), 1), np.int64)
+    best = C.c_int32(-1)
+    rc = lib.slimattn_search_unit_count(_p(L), len(L), C.byref(sp), C.byref(ss), _p(M), len(M), n_threads, _p64(t), _p64(pk), C.byref(best))
+    if rc != 0:
+        raise SlimAttnError(rc, "slimattn_search_unit_count")
+    return t[:len(M)].copy(), pk[:len(M)].copy(), int(best.value)
 
 
 def dag_buffers_1f1b(slices, fwd_units, bwd_units, n_stages: int, act_bytes: int, kv_bytes: int, grad_bytes: int, per_slice: bool = True):

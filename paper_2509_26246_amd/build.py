@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslimattn.so")
-SOURCES = ["builder.cpp", "solver.cpp", "dag.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "fwd_wide_bf16.hip", "bwd_bf16.hip", "dkdv_wide_bf16.hip"]
+SOURCES = ["builder.cpp", "solver.cpp", "dag.cpp", "search.cpp", "tables.cpp", "api.cpp", "kernels_f32.hip", "fwd_bf16.hip", "fwd_wide_bf16.hip", "bwd_bf16.hip", "dkdv_wide_bf16.hip"]
 # dkdv_wide_bf16.hip keeps its dK/dV accumulators in the accumulation registers through inline asm; the
 # builtin products of the same kernel must then be told to stay in architectural registers.
 EXTRA_FLAGS = {"dkdv_wide_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
