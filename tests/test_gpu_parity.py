@@ -299,10 +299,21 @@ FULL_SIZE_CASES = [
 
 @pytest.mark.parametrize("name,modes", FULL_SIZE_CASES, ids=[c[0] for c in FULL_SIZE_CASES])
 def test_full_size_sampled_rows_and_identities(name, modes):
+    _full_size(name, modes, 1)
+
+
+@pytest.mark.parametrize("seed", [s for s in W.SEEDS if s != 1])
+def test_full_size_every_pack_the_benchmark_times(seed):
+    # bench.py cycles over the packs of all seeds of the 32K workload; the case above covers the first
+    _full_size("cfg1_llama8b_32k", ("fused", "per-unit"), seed)
+
+
+def _full_size(name, modes, seed):
     w = W.WORKLOADS[name]
-    rng = np.random.default_rng(1)
+    rng = np.random.default_rng(seed)
     L = W.draw_lengths(w, rng)
     T_ = int(L.sum())
+    name = name if seed == 1 else f"{name}/seed{seed}"
     print(f"[{name}] T {T_} samples {len(L)} longest {int(L.max())}", flush=True)
     q, k, v, dO = W.draw_values(w, T_, rng)
     cu, sl, fu, bu = _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
