@@ -308,15 +308,33 @@ def test_full_size_every_pack_the_benchmark_times(seed):
     _full_size("cfg1_llama8b_32k", ("fused", "per-unit"), seed)
 
 
-def _full_size(name, modes, seed):
+@pytest.mark.parametrize("name,seed", [("cfg1_llama8b_32k", 3), ("cfg2_tail_forced", 1)])
+def test_full_size_with_the_solvers_partition(name, seed):
+    # the tables bench.py's `per_unit_solver` record times: slice boundaries and both unit lists from the exact
+    # partition (non-uniform slices), same unit counts as the policies, cuts on the chip-filling granule
+    _full_size(name, ("fused", "per-unit"), seed, solver=True)
+
+
+def _solver_tables(w, L):
+    _, _, fu, bu = _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
+    granule = max(256, 256 * 128 // max(1, w.n_q_heads // 2))
+    r = S.solve_partition(L, m_fwd=len(fu[0]) - 1, m_bwd=len(bu[0]) - 1, w_quad_fwd=w.fwd_policy[1].get("w_quad", 2),
+                          w_lin_fwd=w.fwd_policy[1].get("w_lin", 0), w_quad_bwd=w.bwd_policy[1].get("w_quad", 5),
+                          w_lin_bwd=w.bwd_policy[1].get("w_lin", 0), granule=granule, max_slice=max(w.slice_size, granule))
+    assert S.validate(r["cu"], r["slices"], *r["fwd"], S.CHECK_FORWARD | S.CHECK_ORDER) == (0, "")
+    assert S.validate(r["cu"], r["slices"], *r["bwd"], S.CHECK_BACKWARD | S.CHECK_ORDER) == (0, "")
+    return r["cu"], r["slices"], r["fwd"], r["bwd"]
+
+
+def _full_size(name, modes, seed, solver=False):
     w = W.WORKLOADS[name]
     rng = np.random.default_rng(seed)
     L = W.draw_lengths(w, rng)
     T_ = int(L.sum())
-    name = name if seed == 1 else f"{name}/seed{seed}"
+    name = (name if seed == 1 else f"{name}/seed{seed}") + ("/solver" if solver else "")
     print(f"[{name}] T {T_} samples {len(L)} longest {int(L.max())}", flush=True)
     q, k, v, dO = W.draw_values(w, T_, rng)
-    cu, sl, fu, bu = _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
+    cu, sl, fu, bu = _solver_tables(w, L) if solver else _tables(L, w.slice_size, w.fwd_policy, w.bwd_policy)
     scale = w.head_dim ** -0.5
     g = w.n_q_heads // w.n_kv_heads
     prob = H.make_problem(q, k, v, dO, cu, sl, fu, bu, bf16=True, scale=scale)
