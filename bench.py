@@ -279,7 +279,7 @@ def main():
         out = {"value": (fwd_flops + bwd_flops) / wall / 1e12, "ms_per_step": wall * 1e3 / max(steps, 1),
                "fwd_tflops": fwd_flops / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0,
                "bwd_tflops": bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0,
-               "kernel_ms_per_step": {c: per[c][0] / max(steps, 1) for c in per if not c.endswith("_call")},
+               "kernel_ms_per_step": {c: per[c][0] / max(steps, 1) for c in per if not c.endswith("_call") and c != "unused"},
                "call_ms_per_step": {"fwd": fwd_ms / max(steps, 1), "bwd": bwd_ms / max(steps, 1)}}
         out["fwd_pct_bf16_peak"] = 100 * out["fwd_tflops"] / BF16_MFMA_PEAK_TFLOPS
         out["bwd_pct_bf16_peak"] = 100 * out["bwd_tflops"] / BF16_MFMA_PEAK_TFLOPS

@@ -385,8 +385,8 @@ int slimattn_bwd_static(const slimattn_params* p, const void* q, const void* k, 
 #define SLIMATTN_K_DELTA     1
 #define SLIMATTN_K_DQ        2
 #define SLIMATTN_K_DKDV      3
-#define SLIMATTN_K_FINALIZE  4          /* the reduction of divided key tiles */
-#define SLIMATTN_K_FILL      5          /* (not launched any more; kept so that class numbers stay put) */
+#define SLIMATTN_K_REDUCE    4          /* the reduction of divided key tiles */
+#define SLIMATTN_K_UNUSED    5          /* (no kernel; kept so that class numbers stay put) */
 #define SLIMATTN_K_FWD_CALL  6          /* a whole slimattn_fwd call, first launch to last, on the caller's stream */
 #define SLIMATTN_K_BWD_CALL  7          /* a whole slimattn_bwd call, likewise (includes the gaps between its launches) */
 #define SLIMATTN_K_COUNT     8

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "slimattn_tables_destroy", "slimattn_tables_count", "slimattn_bwd_workspace_bytes", "slimattn_fwd",
     "slimattn_bwd", "slimattn_bwd_static", "slimattn_bwd_released_rows", "slimattn_strerror", "slimattn_last_hip_error", "slimattn_version", "slimattn_profile_enable",
     "slimattn_profile_read", "slimattn_profile_read_launches"]
-KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "finalize", "fill", "fwd_call", "bwd_call"]
+KERNEL_CLASSES = ["fwd", "delta", "dq", "dkdv", "reduce", "unused", "fwd_call", "bwd_call"]
 
 
 class SlimAttnError(RuntimeError):

@@ -261,7 +261,7 @@ static int bwd_impl(const slimattn_params* p, const void* q, const void* k, cons
     if (e != 0) return e;
     const int ra = L.reduce_off[ti][sc][u], rb = L.reduce_off[ti][sc][u + 1];
     if (rb == ra) return 0;
-    return timed(SLIMATTN_K_FINALIZE, stream, [&] {
+    return timed(SLIMATTN_K_REDUCE, stream, [&] {
       return launch_bwd_reduce_bf16(ctx, parts, acc_dk, acc_dv, dK, dV, D.reduce_items[ti][sc] + ra, rb - ra, tile_rows);
     });
   };
