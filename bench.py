@@ -140,7 +140,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-unit", action="store_true", help="main measurement: one launch per unit instead of one fused launch")
     ap.add_argument("--seeds", default="", help="comma-separated subset of the workload's seeds (default: all four)")
-    ap.add_argument("--brief", action="store_true", help="skip the per-seed and the secondary per-unit measurements")
+    ap.add_argument("--brief", action="store_true", help="the main measurement only: no per-seed values, no secondary per-unit records, no graph replay, no search")
     ap.add_argument("--granule", type=int, default=0,
                     help="solver partition: cuts on multiples of this many rows (default: the rows whose forward work "
                          "items fill the chip once, 256 blocks x 128 rows / head pairs, at least 256)")
@@ -461,8 +461,9 @@ def main():
     if args.per_unit:
         out["unit_ms"] = unit_spread(rec, args.steps)
         out["pipeline_1f1b"] = pipeline_sim(rec)
-        out["hip_graph_replay"] = measure_graph(main_flags, args.steps, min(args.warmup, 4))
-        out["unit_count_search"] = unit_count_search(rec)
+        if not args.brief:
+            out["hip_graph_replay"] = measure_graph(main_flags, args.steps, min(args.warmup, 4))
+            out["unit_count_search"] = unit_count_search(rec)
 
     if not args.brief:
         # every seed's pack on its own (same launch mode as the main measurement), and the median over seeds
